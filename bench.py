@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark of libjigsaw_decode: paged decode attention on one MI355X.
+
+A step is one jd_decode_attention call (work partition + split-KV partial pass + combine) over
+one synthetic decode batch that is already resident in HBM.  The default workload is the
+long-tailed Qwen3-8B-like rollout step (batch 256, 32 q / 8 kv heads, head_dim 128, 16-token
+pages, 512-token prompt + lognormal response); `--cfg` selects another of the five configs.
+
+Prints ONE JSON line: the metric (KV bytes read per second, i.e. T * 2 * Hkv * D * 2 bytes per
+step over the step time), a `roofline` object for the dominant kernel (the partial pass, timed
+with HIP events on the launch stream inside the timed region), and a `cpu_baseline` object (the
+fp64 CPU oracle timed on the host cores on a bounded sample of the same workload).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--cfg", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--variant", type=int, default=0, help="0 default, 1 vector, 2 mfma")
+    ap.add_argument("--cu-budget", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0, help="CPU-seconds budget of the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU by design (decode attention shards by request or by kv head "
+              "with no exchange); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2604_23838_amd import binding as jb
+    from paper_2604_23838_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    dev = torch.device("cuda:0")
+    t0 = time.time()
+    w = W.gen_config(args.cfg, args.seed, threads=min(16, os.cpu_count() or 8))
+    s = w.shape
+    print(f"[bench] generated cfg{args.cfg} ({s.name}) T={w.total_tokens} KV={w.kv_bytes / 1e9:.3f} GB "
+          f"in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+    q = torch.from_numpy(w.q.view(np.int16)).to(dev).view(torch.bfloat16)
+    kp = torch.from_numpy(w.k_pages.view(np.int16)).to(dev).view(torch.bfloat16)
+    vp = torch.from_numpy(w.v_pages.view(np.int16)).to(dev).view(torch.bfloat16)
+    bt = torch.from_numpy(w.block_table).to(dev)
+    sl = torch.from_numpy(w.seq_lens).to(dev)
+    out = torch.empty((s.batch, s.num_q_heads, s.head_dim), dtype=torch.float32, device=dev)
+    op = jb.DecodeAttention(s.batch, s.num_q_heads, s.num_kv_heads, s.head_dim, w.max_pages_per_seq, w.num_pages,
+                            variant=args.variant, cu_budget=args.cu_budget)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for _ in range(args.warmup):
+            op(q, kp, vp, bt, sl, out)
+        torch.cuda.synchronize()
+        jb.jd_profile_enable(op.handle, args.steps)
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for _ in range(args.steps):
+            op(q, kp, vp, bt, sl, out)
+        torch.cuda.synchronize()
+        t_end = time.perf_counter()
+        ms_sum, calls = jb.jd_profile_read(op.handle)
+        jb.jd_profile_enable(op.handle, 0)
+    op.check_flags()
+    ms_per_step = (t_end - t_start) * 1e3 / args.steps
+    kv_bytes = w.kv_bytes
+    tbs = kv_bytes / (ms_per_step * 1e-3) / 1e12
+    partial_ms = ms_sum[1] / max(calls, 1)
+    achieved = kv_bytes / (partial_ms * 1e-3) / 1e9 if partial_ms > 0 else 0.0
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            with open(tpath) as f:
+                traffic = json.load(f).get(f"cfg{args.cfg}_variant{args.variant}")
+        except Exception:
+            traffic = None
+
+    result = {
+        "metric": "decode_attention_kv_bandwidth",
+        "value": round(tbs, 4),
+        "unit": "TB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "us_per_step": round(ms_per_step * 1e3, 2),
+        "pct_of_hbm_peak": round(100.0 * tbs * 1e3 / HBM_PEAK_GBS, 2),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16 in, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"cfg{args.cfg} {s.name}: batch {s.batch}, {s.num_q_heads}q/{s.num_kv_heads}kv heads, "
+                               f"head_dim {s.head_dim}, page 16, seed {args.seed}, T={w.total_tokens} tokens",
+                   "kv_bytes_per_step": kv_bytes, "variant": args.variant, "cu_budget": args.cu_budget,
+                   "derived_us_per_model_step": round(ms_per_step * 1e3 * s.layers, 1), "layers": s.layers},
+        "kernel_ms": {"partition": round(ms_sum[0] / max(calls, 1), 5), "partial": round(partial_ms, 5),
+                      "combine": round(ms_sum[2] / max(calls, 1), 5)},
+        "roofline": {"bound": "hbm", "kernel": "split-KV partial pass", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": traffic},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import jo
+        cores = jo.max_threads()
+        # bounded sample: whole requests, taken in batch order until the CPU-seconds budget is used
+        # (the oracle does ~4*L*Hq*D fp64 flops per request at a few GFLOP/s per core)
+        flops_budget = args.cpu_seconds * 1.0e9
+        rows, used = [], 0.0
+        for b in range(s.batch):
+            f = 4.0 * float(w.seq_lens[b]) * s.num_q_heads * s.head_dim
+            if rows and used + f > flops_budget:
+                break
+            rows.append(b)
+            used += f
+        sub = W.subset_requests(w, rows)
+        t1 = time.perf_counter()
+        ref = jo.decode_attention(sub.q, sub.k_pages, sub.v_pages, sub.block_table, sub.seq_lens)
+        dt = time.perf_counter() - t1
+        got = out[torch.tensor(rows, device=dev)].cpu().numpy()
+        diff = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+        max_abs = float(diff.max())
+        max_rel = float((diff / np.maximum(np.abs(ref.astype(np.float64)), 1e-3)).max())
+        result["cpu_baseline"] = {"value": round(sub.kv_bytes / dt / 1e12, 6), "unit": "TB/s", "cores": cores,
+                                  "kind": "oracle",
+                                  "sample": f"first {len(rows)} of {s.batch} requests ({sub.total_tokens} tokens, "
+                                            f"{sub.kv_bytes / 1e9:.3f} GB of KV), fp64, {dt:.2f}s wall"}
+        result["parity_on_sample"] = {"max_abs": max_abs, "max_rel_floor1e-3": max_rel,
+                                      "ok": bool(max_abs <= 5e-3 and max_rel <= 1e-2)}
+    op.close()
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

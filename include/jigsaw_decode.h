@@ -1,0 +1,158 @@
+/*
+ * jigsaw_decode.h -- C ABI of libjigsaw_decode: paged decode attention for rollout
+ * batches with ragged, long-tailed sequence lengths, on one MI355X (gfx950).
+ *
+ * The operation is the attention part of one rollout decode forward step.  The paper
+ * delegates rollout to an inference engine and prints no attention formula; what it
+ * fixes is the setting this library is built for: every forward step processes the
+ * active decoding requests (System Design, "Sub-Stage Graph Abstraction"), the KV cache
+ * is the memory object that bounds them (Sub-stage Multiplexing, "GPU Memory
+ * Utilization"), decoding is memory-bound (Motivation, "Multi-turn Rollout Idling";
+ * Sub-stage Multiplexing, "Compute Resource Utilization") and a few long sequences
+ * dominate the step while the effective batch shrinks (Motivation, "Varied Decoding
+ * Lengths").  For request b with L = seq_lens[b] tokens, query head h and kv head
+ * kv = h / (num_q_heads / num_kv_heads):
+ *
+ *     s_j   = softmax_scale * <q[b][h], K_j>           j = 0 .. L-1
+ *     out[b][h] = sum_j softmax(s)_j * V_j
+ *
+ * where token j of request b is row (j % 16) of kv head `kv` in physical page
+ * block_table[b][j / 16].  K/V are bf16, products and sums are fp32, out is fp32.
+ *
+ * All pointers passed to jd_decode_attention are DEVICE pointers owned by the caller
+ * (for example PyTorch tensors); the library reads q/k_pages/v_pages/block_table/
+ * seq_lens and writes out.  The handle and a private device workspace are owned by the
+ * library.  No function throws or aborts; every failure is a status code plus a message
+ * retrievable with jd_last_error_string.
+ */
+#ifndef JIGSAW_DECODE_H
+#define JIGSAW_DECODE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct jd_handle jd_handle;
+
+typedef enum {
+    JD_OK = 0,
+    JD_ERR_INVALID_ARG = 1, /* null pointer, misaligned buffer, non-positive size, heads not divisible */
+    JD_ERR_UNSUPPORTED = 2, /* head_dim not in {64,128}, page_size != 16, group size > 16, unknown variant */
+    JD_ERR_HIP = 3,         /* a HIP runtime call or kernel launch failed */
+    JD_ERR_BAD_INPUT = 4    /* device-side check: a page id or sequence length outside the declared bounds */
+} jd_status;
+
+/* Kernel family used for the split-KV partial pass. */
+typedef enum {
+    JD_VARIANT_DEFAULT = 0, /* the library's choice (the fastest measured for the shape) */
+    JD_VARIANT_VECTOR = 1,  /* vector ALU: dot2 products, DPP/shuffle reductions, pages read straight to registers */
+    JD_VARIANT_MFMA = 2     /* GQA group packed into a matrix-core tile, pages staged in LDS by direct loads */
+} jd_variant;
+
+typedef struct {
+    int32_t batch;             /* B: rows of q/out/block_table/seq_lens; requests with seq_len 0 are skipped */
+    int32_t num_q_heads;       /* Hq */
+    int32_t num_kv_heads;      /* Hkv; must divide Hq; query head h reads kv head h / (Hq / Hkv) */
+    int32_t head_dim;          /* D: 64 or 128 */
+    int32_t page_size;         /* tokens per page: 16 */
+    int32_t max_pages_per_seq; /* MAXP: row stride (in entries) of block_table */
+    int32_t num_pages;         /* NP: pages in k_pages / v_pages; page ids are checked against it */
+    float softmax_scale;       /* 0 means 1 / sqrt(D) */
+    int32_t variant;           /* a jd_variant */
+    int32_t cu_budget;         /* 0: all compute units; otherwise the number of workgroup slots the partial pass
+                                  may occupy (spatial sharing with a co-located job; Sub-stage Multiplexing,
+                                  "Dynamic Resource Allocation") */
+} jd_config;
+
+/*
+ * Pure host check of a configuration; touches no GPU.  Returns JD_OK, JD_ERR_INVALID_ARG
+ * or JD_ERR_UNSUPPORTED.
+ */
+jd_status jd_validate_config(const jd_config *cfg);
+
+/*
+ * Bytes of device workspace a handle for `cfg` holds (work-partition tables and split-KV
+ * partial states).  Pure host function; 0 if cfg is invalid.
+ */
+size_t jd_workspace_bytes(const jd_config *cfg);
+
+/*
+ * Create a handle on the current HIP device.  Validates cfg (no GPU touched on failure),
+ * then allocates the workspace once with hipMalloc.  *out is set only on JD_OK.
+ */
+jd_status jd_create(const jd_config *cfg, jd_handle **out);
+
+/*
+ * One decode step's attention for the whole batch (one transformer layer).
+ *   q           bf16 [B, Hq, D]            device, 16-byte aligned, read
+ *   k_pages     bf16 [NP, Hkv, 16, D]      device, 16-byte aligned, read
+ *   v_pages     bf16 [NP, Hkv, 16, D]      device, 16-byte aligned, read
+ *   block_table int32 [B, MAXP]            device, read; entry j of row b is the physical page of tokens
+ *                                          16j..16j+15; entries at or beyond ceil(L/16) are never read
+ *   seq_lens    int32 [B]                  device, read; tokens per request INCLUDING the one being decoded
+ *                                          (its K/V are already in the cache); <= 0 gives a zero output row
+ *   out         fp32 [B, Hq, D]            device, 16-byte aligned, written (every row)
+ *   stream      a hipStream_t (NULL = the default stream)
+ * Slots beyond L in a last page, pages no request owns and unused block-table entries never
+ * influence the result, whatever bits they hold.  The call only enqueues work (work partition,
+ * split-KV partial pass, log-sum-exp combine) on `stream`; it performs no allocation, no host
+ * synchronisation and no device-to-host copy, so it may be captured into a HIP graph.  Calls on
+ * one handle share its workspace: they must be ordered on one stream (or otherwise serialised).
+ * Page ids outside [0, NP) and lengths beyond 16*MAXP are never dereferenced: the offending page is
+ * replaced by page 0 / the length clamped (the affected rows are then meaningless) and a sticky flag
+ * is raised that jd_check_device_flags reports.
+ */
+jd_status jd_decode_attention(jd_handle *h, const void *q, const void *k_pages, const void *v_pages,
+                              const int32_t *block_table, const int32_t *seq_lens, float *out,
+                              void *stream);
+
+/*
+ * Synchronise `stream` and report device-side input checks of the calls completed so far:
+ * JD_OK, JD_ERR_BAD_INPUT (and clears the flag) or JD_ERR_HIP.
+ */
+jd_status jd_check_device_flags(jd_handle *h, void *stream);
+
+/*
+ * Run only the work partitioner for seq_lens (device, int32 [B]) and copy its tables to the
+ * host (synchronises `stream`).  For tests and tuning.
+ *   header_host      int32 [8]: {units, span, active_waves, wave_slots, nonempty_requests, 0, 0, 0}
+ *                    units = sum over requests of ceil(L/16) * Hkv page-units of work;
+ *                    span = page-units per wave; wave w < active_waves owns units [w*span, min((w+1)*span, units))
+ *   wave_start_host  int32 [wave_slots * 4]: {request, kv_head, page, 0} of the first unit of each active wave
+ *   cum_pages_host   int32 [B + 1]: pages of all requests before b (exclusive prefix of ceil(L/16))
+ * Any of the three host pointers may be NULL.
+ */
+jd_status jd_debug_partition(jd_handle *h, const int32_t *seq_lens, int32_t *header_host,
+                             int32_t *wave_start_host, int32_t *cum_pages_host, void *stream);
+
+/*
+ * Per-kernel timing with HIP events, for benchmarks.  jd_profile_enable creates 4 * max_calls
+ * events (max_calls = 0 frees them and switches timing off); while enabled, each of the next
+ * max_calls jd_decode_attention calls records an event before and after each of its three
+ * kernels on the call's stream (do not capture such calls into a graph).  jd_profile_read
+ * synchronises on the last recorded event, stores the summed durations in milliseconds of
+ * {work partition, split-KV partial pass, combine} and the number of calls summed, and
+ * restarts the recording window.
+ */
+jd_status jd_profile_enable(jd_handle *h, int32_t max_calls);
+jd_status jd_profile_read(jd_handle *h, float ms_sum[3], int32_t *calls);
+
+/* Number of wave slots the partial pass of this handle is launched with (grid waves). */
+int32_t jd_wave_slots(const jd_handle *h);
+
+/* Free the workspace and the handle.  NULL is accepted. */
+jd_status jd_destroy(jd_handle *h);
+
+/*
+ * Message of the last failure on this handle; with NULL, of the last failed jd_create /
+ * jd_validate_config on the calling thread.  Never NULL; valid until the next call.
+ */
+const char *jd_last_error_string(const jd_handle *h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JIGSAW_DECODE_H */

@@ -1,0 +1,205 @@
+"""ctypes binding of libjigsaw_decode (argument marshalling only; every step runs in the HIP kernels).
+
+The functions carry the C ABI's names and take raw device addresses (ints).  `DecodeAttention`
+is a thin convenience wrapper for PyTorch tensors: PyTorch supplies device memory and streams,
+nothing else.  If the shared library is missing, loading raises: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libjigsaw_decode.so")
+
+JD_OK, JD_ERR_INVALID_ARG, JD_ERR_UNSUPPORTED, JD_ERR_HIP, JD_ERR_BAD_INPUT = range(5)
+JD_VARIANT_DEFAULT, JD_VARIANT_VECTOR, JD_VARIANT_MFMA = range(3)
+
+EXPORTS = ("jd_validate_config", "jd_workspace_bytes", "jd_create", "jd_decode_attention",
+           "jd_check_device_flags", "jd_debug_partition", "jd_profile_enable", "jd_profile_read",
+           "jd_wave_slots", "jd_destroy",
+           "jd_last_error_string")
+
+
+class jd_config(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("page_size", C.c_int32), ("max_pages_per_seq", C.c_int32),
+                ("num_pages", C.c_int32), ("softmax_scale", C.c_float), ("variant", C.c_int32),
+                ("cu_budget", C.c_int32)]
+
+
+class JdError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"libjigsaw_decode status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built (python -m paper_2604_23838_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2604_23838_amd.build); "
+                               "there is no fallback implementation")
+        l = C.CDLL(LIB_PATH)
+        vp = C.c_void_p
+        l.jd_validate_config.argtypes = [C.POINTER(jd_config)]
+        l.jd_validate_config.restype = C.c_int
+        l.jd_workspace_bytes.argtypes = [C.POINTER(jd_config)]
+        l.jd_workspace_bytes.restype = C.c_size_t
+        l.jd_create.argtypes = [C.POINTER(jd_config), C.POINTER(vp)]
+        l.jd_create.restype = C.c_int
+        l.jd_decode_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
+        l.jd_decode_attention.restype = C.c_int
+        l.jd_check_device_flags.argtypes = [vp, vp]
+        l.jd_check_device_flags.restype = C.c_int
+        l.jd_debug_partition.argtypes = [vp, vp, vp, vp, vp, vp]
+        l.jd_debug_partition.restype = C.c_int
+        l.jd_profile_enable.argtypes = [vp, C.c_int32]
+        l.jd_profile_enable.restype = C.c_int
+        l.jd_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+        l.jd_profile_read.restype = C.c_int
+        l.jd_wave_slots.argtypes = [vp]
+        l.jd_wave_slots.restype = C.c_int32
+        l.jd_destroy.argtypes = [vp]
+        l.jd_destroy.restype = C.c_int
+        l.jd_last_error_string.argtypes = [vp]
+        l.jd_last_error_string.restype = C.c_char_p
+        _lib = l
+    return _lib
+
+
+def jd_last_error_string(handle=None) -> str:
+    return lib().jd_last_error_string(handle).decode()
+
+
+def jd_validate_config(cfg: jd_config) -> int:
+    return lib().jd_validate_config(C.byref(cfg))
+
+
+def jd_workspace_bytes(cfg: jd_config) -> int:
+    return int(lib().jd_workspace_bytes(C.byref(cfg)))
+
+
+def jd_create(cfg: jd_config):
+    h = C.c_void_p()
+    st = lib().jd_create(C.byref(cfg), C.byref(h))
+    if st != JD_OK:
+        raise JdError(st, jd_last_error_string(None))
+    return h
+
+
+def jd_decode_attention(handle, q, k_pages, v_pages, block_table, seq_lens, out, stream=0) -> None:
+    """All tensor arguments are device addresses (ints); `stream` is a hipStream_t value."""
+    st = lib().jd_decode_attention(handle, q, k_pages, v_pages, block_table, seq_lens, out, stream)
+    if st != JD_OK:
+        raise JdError(st, jd_last_error_string(handle))
+
+
+def jd_check_device_flags(handle, stream=0) -> None:
+    st = lib().jd_check_device_flags(handle, stream)
+    if st != JD_OK:
+        raise JdError(st, jd_last_error_string(handle))
+
+
+def jd_wave_slots(handle) -> int:
+    return int(lib().jd_wave_slots(handle))
+
+
+def jd_debug_partition(handle, seq_lens, batch: int, stream=0):
+    """Returns (header[8], wave_start[slots,4], cum_pages[batch+1]) as lists of ints."""
+    slots = jd_wave_slots(handle)
+    hdr = (C.c_int32 * 8)()
+    ws = (C.c_int32 * (4 * slots))()
+    cum = (C.c_int32 * (batch + 1))()
+    st = lib().jd_debug_partition(handle, seq_lens, C.cast(hdr, C.c_void_p), C.cast(ws, C.c_void_p),
+                                  C.cast(cum, C.c_void_p), stream)
+    if st != JD_OK:
+        raise JdError(st, jd_last_error_string(handle))
+    w = list(ws)
+    return list(hdr), [w[4 * i:4 * i + 4] for i in range(slots)], list(cum)
+
+
+def jd_profile_enable(handle, max_calls: int) -> None:
+    st = lib().jd_profile_enable(handle, max_calls)
+    if st != JD_OK:
+        raise JdError(st, jd_last_error_string(handle))
+
+
+def jd_profile_read(handle):
+    """Returns ([ms_partition, ms_partial, ms_combine] summed over the recorded calls, calls)."""
+    ms = (C.c_float * 3)()
+    n = C.c_int32()
+    st = lib().jd_profile_read(handle, ms, C.byref(n))
+    if st != JD_OK:
+        raise JdError(st, jd_last_error_string(handle))
+    return [float(x) for x in ms], int(n.value)
+
+
+def jd_destroy(handle) -> None:
+    st = lib().jd_destroy(handle)
+    if st != JD_OK:
+        raise JdError(st, jd_last_error_string(None))
+
+
+class DecodeAttention:
+    """Handle plus tensor marshalling for PyTorch callers.
+
+    q, k_pages, v_pages are torch.bfloat16 CUDA tensors in the library layouts
+    ([B,Hq,D], [NP,Hkv,16,D]); block_table and seq_lens are int32 CUDA tensors;
+    out is a float32 CUDA tensor [B,Hq,D] (allocated here when not given).
+    """
+
+    def __init__(self, batch, num_q_heads, num_kv_heads, head_dim, max_pages_per_seq, num_pages, *,
+                 page_size=16, softmax_scale=0.0, variant=JD_VARIANT_DEFAULT, cu_budget=0):
+        self.cfg = jd_config(batch, num_q_heads, num_kv_heads, head_dim, page_size, max_pages_per_seq,
+                             num_pages, softmax_scale, variant, cu_budget)
+        self.handle = jd_create(self.cfg)
+
+    def _check(self, q, k_pages, v_pages, block_table, seq_lens, out):
+        import torch
+        c = self.cfg
+        want = [(q, torch.bfloat16, (c.batch, c.num_q_heads, c.head_dim)),
+                (k_pages, torch.bfloat16, (c.num_pages, c.num_kv_heads, c.page_size, c.head_dim)),
+                (v_pages, torch.bfloat16, (c.num_pages, c.num_kv_heads, c.page_size, c.head_dim)),
+                (block_table, torch.int32, (c.batch, c.max_pages_per_seq)),
+                (seq_lens, torch.int32, (c.batch,)),
+                (out, torch.float32, (c.batch, c.num_q_heads, c.head_dim))]
+        for t, dt, shape in want:
+            if not (t.is_cuda and t.dtype == dt and tuple(t.shape) == shape and t.is_contiguous()):
+                raise ValueError(f"expected contiguous CUDA {dt} tensor of shape {shape}, got {t.dtype} {tuple(t.shape)}")
+
+    def __call__(self, q, k_pages, v_pages, block_table, seq_lens, out=None, stream=None):
+        import torch
+        if out is None:
+            out = torch.empty((self.cfg.batch, self.cfg.num_q_heads, self.cfg.head_dim),
+                              dtype=torch.float32, device=q.device)
+        self._check(q, k_pages, v_pages, block_table, seq_lens, out)
+        s = torch.cuda.current_stream() if stream is None else stream
+        jd_decode_attention(self.handle, q.data_ptr(), k_pages.data_ptr(), v_pages.data_ptr(),
+                            block_table.data_ptr(), seq_lens.data_ptr(), out.data_ptr(), s.cuda_stream)
+        return out
+
+    def check_flags(self, stream=None):
+        import torch
+        s = torch.cuda.current_stream() if stream is None else stream
+        jd_check_device_flags(self.handle, s.cuda_stream)
+
+    def partition(self, seq_lens, stream=None):
+        import torch
+        s = torch.cuda.current_stream() if stream is None else stream
+        return jd_debug_partition(self.handle, seq_lens.data_ptr(), self.cfg.batch, s.cuda_stream)
+
+    def close(self):
+        if self.handle is not None:
+            jd_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

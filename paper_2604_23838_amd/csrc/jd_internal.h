@@ -1,0 +1,57 @@
+// Internal declarations shared by the translation units of libjigsaw_decode.
+// Nothing here is part of the C ABI (see include/jigsaw_decode.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace jd {
+
+constexpr int kPage = 16;          // tokens per KV page
+constexpr int kMinSpan = 4;        // smallest share of work (page-units) a wave is given
+constexpr int kMaxWaveSlots = 4096;
+constexpr int kHeaderInts = 64;
+
+// Header words of the work-partition table (device, int32).
+enum HeaderWord {
+    kHdrUnits = 0,      // page-units of work: sum_b ceil(L_b/16) * Hkv
+    kHdrSpan = 1,       // page-units per wave
+    kHdrActive = 2,     // waves that own at least one unit
+    kHdrSlots = 3,      // wave slots the partial pass is launched with
+    kHdrNonEmpty = 4,   // requests with at least one token
+    kHdrBadInput = 5,   // sticky flag: page id or length out of bounds seen
+};
+
+// Device pointers and sizes every kernel receives by value.
+struct Params {
+    const uint16_t* q;          // bf16 [B, Hq, D]
+    const uint16_t* k_pages;    // bf16 [NP, Hkv, 16, D]
+    const uint16_t* v_pages;    // bf16 [NP, Hkv, 16, D]
+    const int32_t* block_table; // [B, MAXP]
+    const int32_t* seq_lens;    // [B]
+    float* out;                 // fp32 [B, Hq, D]
+    // workspace
+    int32_t* header;            // [kHeaderInts]
+    int32_t* cum_pages;         // [B + 1] exclusive prefix of pages per request
+    int32_t* rank;              // [B] index of request b among the non-empty ones
+    int32_t* req;               // [B] request id of the r-th non-empty request
+    int32_t* wave_start;        // [slots * 4] {r, kv, page, 0}
+    float* partials;            // [slots * 2] records of G*(D+2) floats: acc[G][D], m[G], l[G]
+    int32_t B, Hq, Hkv, G, D, maxp, NP, slots;
+    float scale_log2e;          // softmax_scale * log2(e): scores are kept in the exp2 domain
+};
+
+inline __host__ __device__ int record_floats(int G, int D) { return G * (D + 2); }
+
+// Launchers (each enqueues on `stream` and returns hipGetLastError()).
+hipError_t launch_partition(const Params& p, hipStream_t stream);
+hipError_t launch_partial_vector(const Params& p, hipStream_t stream);
+hipError_t launch_partial_mfma(const Params& p, hipStream_t stream);
+hipError_t launch_combine(const Params& p, hipStream_t stream);
+
+// Wave slots each variant wants per compute unit.
+int vector_waves_per_cu();
+int mfma_waves_per_cu();
+int vector_waves_per_block();
+int mfma_waves_per_block();
+
+}  // namespace jd
