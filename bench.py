@@ -78,6 +78,19 @@ def main() -> int:
         t_end = time.perf_counter()
         ms_sum, calls = jb.jd_profile_read(op.handle)
         jb.jd_profile_enable(op.handle, 0)
+    # measured ceiling of a plain read sweep over the K pool (same stream, same process)
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    nbytes = kp.numel() * 2
+    with torch.cuda.stream(stream):
+        for _ in range(3):
+            jb.jd_debug_stream_read(kp.data_ptr(), nbytes, sink.data_ptr(), stream.cuda_stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(20):
+            jb.jd_debug_stream_read(kp.data_ptr(), nbytes, sink.data_ptr(), stream.cuda_stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+    read_ceiling = nbytes * 20 / (e0.elapsed_time(e1) * 1e-3) / 1e9
     op.check_flags()
     ms_per_step = (t_end - t_start) * 1e3 / args.steps
     kv_bytes = w.kv_bytes
@@ -104,6 +117,8 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 5),
         "us_per_step": round(ms_per_step * 1e3, 2),
         "pct_of_hbm_peak": round(100.0 * tbs * 1e3 / HBM_PEAK_GBS, 2),
+        "stream_read_ceiling_gbs": round(read_ceiling, 1),
+        "pct_of_stream_read_ceiling": round(100.0 * tbs * 1e3 / read_ceiling, 2),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -134,9 +149,13 @@ def main() -> int:
             rows.append(b)
             used += f
         sub = W.subset_requests(w, rows)
-        t1 = time.perf_counter()
-        ref = jo.decode_attention(sub.q, sub.k_pages, sub.v_pages, sub.block_table, sub.seq_lens)
-        dt = time.perf_counter() - t1
+        passes, dt = 0, 0.0
+        while passes == 0 or (dt * cores < 0.75 * args.cpu_seconds and passes < 16):
+            t1 = time.perf_counter()
+            ref = jo.decode_attention(sub.q, sub.k_pages, sub.v_pages, sub.block_table, sub.seq_lens)
+            dt += time.perf_counter() - t1
+            passes += 1
+        dt /= passes
         got = out[torch.tensor(rows, device=dev)].cpu().numpy()
         diff = np.abs(got.astype(np.float64) - ref.astype(np.float64))
         max_abs = float(diff.max())
@@ -144,7 +163,8 @@ def main() -> int:
         result["cpu_baseline"] = {"value": round(sub.kv_bytes / dt / 1e12, 6), "unit": "TB/s", "cores": cores,
                                   "kind": "oracle",
                                   "sample": f"first {len(rows)} of {s.batch} requests ({sub.total_tokens} tokens, "
-                                            f"{sub.kv_bytes / 1e9:.3f} GB of KV), fp64, {dt:.2f}s wall"}
+                                            f"{sub.kv_bytes / 1e9:.3f} GB of KV), fp64, {passes} passes, "
+                                            f"{dt:.2f}s wall each"}
         result["parity_on_sample"] = {"max_abs": max_abs, "max_rel_floor1e-3": max_rel,
                                       "ok": bool(max_abs <= 5e-3 and max_rel <= 1e-2)}
     op.close()

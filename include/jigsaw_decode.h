@@ -140,6 +140,15 @@ jd_status jd_debug_partition(jd_handle *h, const int32_t *seq_lens, int32_t *hea
 jd_status jd_profile_enable(jd_handle *h, int32_t max_calls);
 jd_status jd_profile_read(jd_handle *h, float ms_sum[3], int32_t *calls);
 
+/*
+ * Plain streaming kernels of known HBM traffic, for benchmarks and for scaling profiler byte
+ * counters: a read-only sweep of `bytes` bytes at src (sink: 4 writable device bytes, practically
+ * never written) and a copy of `bytes` bytes.  Device pointers, 16-byte aligned; bytes is rounded
+ * down to a multiple of 16.  They only enqueue on `stream`.
+ */
+jd_status jd_debug_stream_read(const void *src, size_t bytes, void *sink, void *stream);
+jd_status jd_debug_stream_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 /* Number of wave slots the partial pass of this handle is launched with (grid waves). */
 int32_t jd_wave_slots(const jd_handle *h);
 

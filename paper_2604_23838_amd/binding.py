@@ -17,6 +17,7 @@ JD_VARIANT_DEFAULT, JD_VARIANT_VECTOR, JD_VARIANT_MFMA = range(3)
 
 EXPORTS = ("jd_validate_config", "jd_workspace_bytes", "jd_create", "jd_decode_attention",
            "jd_check_device_flags", "jd_debug_partition", "jd_profile_enable", "jd_profile_read",
+           "jd_debug_stream_read", "jd_debug_stream_copy",
            "jd_wave_slots", "jd_destroy",
            "jd_last_error_string")
 
@@ -62,6 +63,10 @@ def lib():
         l.jd_profile_enable.restype = C.c_int
         l.jd_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
         l.jd_profile_read.restype = C.c_int
+        l.jd_debug_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
+        l.jd_debug_stream_read.restype = C.c_int
+        l.jd_debug_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
+        l.jd_debug_stream_copy.restype = C.c_int
         l.jd_wave_slots.argtypes = [vp]
         l.jd_wave_slots.restype = C.c_int32
         l.jd_destroy.argtypes = [vp]
@@ -137,6 +142,18 @@ def jd_profile_read(handle):
     if st != JD_OK:
         raise JdError(st, jd_last_error_string(handle))
     return [float(x) for x in ms], int(n.value)
+
+
+def jd_debug_stream_read(src, nbytes: int, sink, stream=0) -> None:
+    st = lib().jd_debug_stream_read(src, nbytes, sink, stream)
+    if st != JD_OK:
+        raise JdError(st, "jd_debug_stream_read failed")
+
+
+def jd_debug_stream_copy(dst, src, nbytes: int, stream=0) -> None:
+    st = lib().jd_debug_stream_copy(dst, src, nbytes, stream)
+    if st != JD_OK:
+        raise JdError(st, "jd_debug_stream_copy failed")
 
 
 def jd_destroy(handle) -> None:

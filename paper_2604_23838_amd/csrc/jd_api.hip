@@ -70,6 +70,7 @@ jd_status validate(const jd_config* c, std::string& msg)
     const long long line = static_cast<long long>(c->batch) * c->max_pages_per_seq * c->num_kv_heads;
     if (line >= (1ll << 31)) { msg = "batch * max_pages_per_seq * num_kv_heads must stay below 2^31"; return JD_ERR_INVALID_ARG; }
     if (static_cast<long long>(c->batch) * c->num_q_heads >= (1ll << 31)) { msg = "batch * num_q_heads must stay below 2^31"; return JD_ERR_INVALID_ARG; }
+    if (static_cast<long long>(c->num_pages) * c->num_kv_heads >= (1ll << 31)) { msg = "num_pages * num_kv_heads must stay below 2^31"; return JD_ERR_INVALID_ARG; }
     if (c->head_dim != 64 && c->head_dim != 128) { msg = "head_dim must be 64 or 128"; return JD_ERR_UNSUPPORTED; }
     if (c->page_size != jd::kPage) { msg = "page_size must be 16"; return JD_ERR_UNSUPPORTED; }
     const int G = c->num_q_heads / c->num_kv_heads;
@@ -86,7 +87,7 @@ jd_status validate(const jd_config* c, std::string& msg)
 int resolve_variant(const jd_config& c)
 {
     if (c.variant != JD_VARIANT_DEFAULT) return c.variant;
-    return vector_supports(c.num_q_heads / c.num_kv_heads) ? JD_VARIANT_VECTOR : JD_VARIANT_MFMA;
+    return JD_VARIANT_MFMA;  // measured faster than the vector variant on every benchmark shape
 }
 
 // Wave slots for a handle: waves per CU of the variant times the CU budget, a multiple of the block size.
