@@ -49,7 +49,8 @@ typedef enum {
 typedef enum {
     JD_VARIANT_DEFAULT = 0, /* the library's choice (the fastest measured for the shape) */
     JD_VARIANT_VECTOR = 1,  /* vector ALU: dot2 products, DPP/shuffle reductions, pages read straight to registers */
-    JD_VARIANT_MFMA = 2     /* GQA group packed into a matrix-core tile, pages staged in LDS by direct loads */
+    JD_VARIANT_MFMA = 2     /* GQA group packed into a matrix-core tile, pages staged in LDS by direct loads;
+                               partition, partial pass and combine fused into one launch */
 } jd_variant;
 
 typedef struct {
@@ -118,10 +119,11 @@ jd_status jd_check_device_flags(jd_handle *h, void *stream);
 /*
  * Run only the work partitioner for seq_lens (device, int32 [B]) and copy its tables to the
  * host (synchronises `stream`).  For tests and tuning.
- *   header_host      int32 [8]: {units, span, active_waves, wave_slots, nonempty_requests, 0, 0, 0}
+ *   header_host      int32 [8]: {units, span, active_waves, wave_slots, 0, 0, 0, 0}
  *                    units = sum over requests of ceil(L/16) * Hkv page-units of work;
  *                    span = page-units per wave; wave w < active_waves owns units [w*span, min((w+1)*span, units))
  *   wave_start_host  int32 [wave_slots * 4]: {request, kv_head, page, 0} of the first unit of each active wave
+ *                    (zeros for the inactive ones)
  *   cum_pages_host   int32 [B + 1]: pages of all requests before b (exclusive prefix of ceil(L/16))
  * Any of the three host pointers may be NULL.
  */
@@ -135,7 +137,8 @@ jd_status jd_debug_partition(jd_handle *h, const int32_t *seq_lens, int32_t *hea
  * kernels on the call's stream (do not capture such calls into a graph).  jd_profile_read
  * synchronises on the last recorded event, stores the summed durations in milliseconds of
  * {work partition, split-KV partial pass, combine} and the number of calls summed, and
- * restarts the recording window.
+ * restarts the recording window.  The matrix-core variant runs all three phases in one fused
+ * kernel: its whole duration is reported under the partial pass, the other two read 0.
  */
 jd_status jd_profile_enable(jd_handle *h, int32_t max_calls);
 jd_status jd_profile_read(jd_handle *h, float ms_sum[3], int32_t *calls);

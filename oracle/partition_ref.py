@@ -21,8 +21,8 @@ def pages(L: int, max_pages: int) -> int:
 
 def partition(seq_lens, num_kv_heads: int, slots: int, max_pages: int, min_span: int = 4):
     """Returns (header, wave_start, cum_pages) as the library reports them:
-    header = [units, span, active_waves, slots, nonempty_requests];
-    wave_start[w] = [rank of request among non-empty ones, kv head, page, 0] for w < active_waves."""
+    header = [units, span, active_waves, slots];
+    wave_start[w] = [request, kv head, page, 0] for w < active_waves."""
     n = [pages(int(L), max_pages) for L in seq_lens]
     cum = [0]
     for x in n:
@@ -30,18 +30,14 @@ def partition(seq_lens, num_kv_heads: int, slots: int, max_pages: int, min_span:
     units = cum[-1] * num_kv_heads
     span = max(min_span, -(-units // slots))
     active = -(-units // span)
-    rank, r = [], 0
-    for x in n:
-        rank.append(r)
-        r += 1 if x > 0 else 0
     # enumerate the line explicitly and read off where each wave starts
     starts = []
     line = ((b, kv, pg) for b in range(len(n)) for kv in range(num_kv_heads) for pg in range(n[b]))
     for u, (b, kv, pg) in enumerate(line):
         if u % span == 0:
-            starts.append([rank[b], kv, pg, 0])
+            starts.append([b, kv, pg, 0])
     assert len(starts) == active
-    return [units, span, active, slots, r], starts, cum
+    return [units, span, active, slots], starts, cum
 
 
 def segments(seq_lens, num_kv_heads: int, slots: int, max_pages: int, min_span: int = 4):

@@ -10,7 +10,8 @@ import ctypes as C
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libjigsaw_decode.so")
+# JIGSAW_DECODE_LIB points tuning runs at an alternative build of the same library
+LIB_PATH = os.environ.get("JIGSAW_DECODE_LIB") or os.path.join(_HERE, "libjigsaw_decode.so")
 
 JD_OK, JD_ERR_INVALID_ARG, JD_ERR_UNSUPPORTED, JD_ERR_HIP, JD_ERR_BAD_INPUT = range(5)
 JD_VARIANT_DEFAULT, JD_VARIANT_VECTOR, JD_VARIANT_MFMA = range(3)

@@ -27,7 +27,7 @@ namespace {
 thread_local std::string g_error = "no error";
 
 struct Layout {
-    size_t header, cum, rank, req, wave_start, partials, total;
+    size_t header, cum, rank, req, wave_start, counters, partials, total;
 };
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -41,6 +41,7 @@ Layout make_layout(const jd_config& c, int slots)
     l.rank = off; off = align_up(off + sizeof(int32_t) * static_cast<size_t>(c.batch), 256);
     l.req = off; off = align_up(off + sizeof(int32_t) * static_cast<size_t>(c.batch), 256);
     l.wave_start = off; off = align_up(off + sizeof(int32_t) * 4 * static_cast<size_t>(slots), 256);
+    l.counters = off; off = align_up(off + sizeof(int32_t) * static_cast<size_t>(c.batch) * c.num_kv_heads, 256);
     const int G = c.num_q_heads / c.num_kv_heads;
     l.partials = off;
     off = align_up(off + sizeof(float) * 2 * static_cast<size_t>(slots) * jd::record_floats(G, c.head_dim), 256);
@@ -80,6 +81,9 @@ jd_status validate(const jd_config* c, std::string& msg)
     }
     if (c->variant == JD_VARIANT_VECTOR && !vector_supports(G)) {
         msg = "the vector variant supports group sizes 1, 2, 4, 7 and 8"; return JD_ERR_UNSUPPORTED;
+    }
+    if (c->variant != JD_VARIANT_VECTOR && c->batch > jd::mfma_max_batch()) {
+        msg = "the matrix-core variant supports batches up to 32768"; return JD_ERR_UNSUPPORTED;
     }
     return JD_OK;
 }
@@ -163,6 +167,7 @@ jd_status jd_create(const jd_config* cfg, jd_handle** out)
     p.rank = reinterpret_cast<int32_t*>(ws + lay.rank);
     p.req = reinterpret_cast<int32_t*>(ws + lay.req);
     p.wave_start = reinterpret_cast<int32_t*>(ws + lay.wave_start);
+    p.counters = reinterpret_cast<int32_t*>(ws + lay.counters);
     p.partials = reinterpret_cast<float*>(ws + lay.partials);
     p.B = cfg->batch; p.Hq = cfg->num_q_heads; p.Hkv = cfg->num_kv_heads;
     p.G = p.Hq / p.Hkv; p.D = cfg->head_dim; p.maxp = cfg->max_pages_per_seq; p.NP = cfg->num_pages;
@@ -192,13 +197,13 @@ jd_status jd_decode_attention(jd_handle* h, const void* q, const void* k_pages, 
     p.out = out;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipEvent_t* ev = (h->prof_calls < h->prof_max) ? &h->events[4 * h->prof_calls] : nullptr;
+    const bool fused = h->variant != JD_VARIANT_VECTOR;  // one launch does partition, partial pass and combine
     hipError_t e = ev ? hipEventRecord(ev[0], s) : hipSuccess;
-    if (e == hipSuccess) e = jd::launch_partition(p, s);
+    if (e == hipSuccess && !fused) e = jd::launch_partition(p, s);
     if (e == hipSuccess && ev) e = hipEventRecord(ev[1], s);
-    if (e == hipSuccess)
-        e = h->variant == JD_VARIANT_VECTOR ? jd::launch_partial_vector(p, s) : jd::launch_partial_mfma(p, s);
+    if (e == hipSuccess) e = fused ? jd::launch_fused_mfma(p, s, 0) : jd::launch_partial_vector(p, s);
     if (e == hipSuccess && ev) e = hipEventRecord(ev[2], s);
-    if (e == hipSuccess) e = jd::launch_combine(p, s);
+    if (e == hipSuccess && !fused) e = jd::launch_combine(p, s);
     if (e == hipSuccess && ev) { e = hipEventRecord(ev[3], s); ++h->prof_calls; }
     if (e != hipSuccess) return fail(h, JD_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
     return JD_OK;
@@ -231,7 +236,7 @@ jd_status jd_debug_partition(jd_handle* h, const int32_t* seq_lens, int32_t* hea
     jd::Params p = h->params;
     p.seq_lens = seq_lens;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = jd::launch_partition(p, s);
+    hipError_t e = h->variant == JD_VARIANT_VECTOR ? jd::launch_partition(p, s) : jd::launch_fused_mfma(p, s, 1);
     int32_t hdr[8] = {0};
     if (e == hipSuccess) e = hipMemcpyAsync(hdr, p.header, sizeof hdr, hipMemcpyDeviceToHost, s);
     if (e == hipSuccess && wave_start_host)
@@ -242,7 +247,15 @@ jd_status jd_debug_partition(jd_handle* h, const int32_t* seq_lens, int32_t* hea
     if (e != hipSuccess) return fail(h, JD_ERR_HIP, std::string("partition failed: ") + hipGetErrorString(e));
     if (header_host) {
         std::memcpy(header_host, hdr, sizeof hdr);
-        header_host[5] = header_host[6] = header_host[7] = 0;
+        header_host[4] = header_host[5] = header_host[6] = header_host[7] = 0;
+    }
+    if (wave_start_host) {  // report {request, kv head, page, 0}
+        for (int w = 0; w < p.slots; ++w) {
+            int32_t* r = wave_start_host + 4 * w;
+            r[0] = w < hdr[jd::kHdrActive] ? r[3] : 0;
+            if (w >= hdr[jd::kHdrActive]) r[1] = r[2] = 0;
+            r[3] = 0;
+        }
     }
     return JD_OK;
 }

@@ -1,0 +1,726 @@
+// Fused decode-attention kernel, matrix-core variant: work partition, split-KV partial
+// attention and log-sum-exp combine in ONE launch.
+//
+// Prologue (work partition).  Every block scans seq_lens in LDS (exclusive prefix of pages
+// per request) and each wave finds, by binary search, the (request, kv head, page) at
+// which its equal share of the work line begins.  The scan is repeated by every block
+// instead of being produced by a separate kernel: it costs a few KiB of L2 reads and
+// removes a launch and a dependency from the critical path of short steps.  Rows of empty
+// requests are zeroed here.
+//
+// Main loop (split-KV partial attention).  Each wave streams the KV pages of its span
+// through a private ring of LDS stages.  A stage holds one 16-token page of K and of V for
+// one kv head (D*32 bytes each) and, when the page opens a segment, the G query rows of
+// that kv head.  Pages are moved HBM -> LDS by direct loads (16 bytes per lane, 1 KiB per
+// instruction, fully coalesced) that bypass the vector registers, so the bytes a wave keeps
+// in flight are set by the ring depth, not by register pressure; a wave only ever waits on
+// the vector-memory counter for the oldest stage while the younger ones stay in flight.
+// Block-table entries are fetched through the scalar data path one page ahead.
+//
+// Per page the GQA group is packed into matrix-core tiles (query rows padded to 16):
+//   S^T[token][q]  = K[token][:] . Q[q][:]         D/32 x  v_mfma_f32_16x16x32_bf16
+//   O^T[d][q]     += V^T[d][token] . P^T[token][q]  D/16 x  v_mfma_f32_16x16x16_bf16
+// The accumulator layout of the first product (lane = query row, 4 consecutive tokens per
+// lane) is exactly the B-operand layout of the second, so the probabilities never leave
+// the registers; V is stored token-major, and the transposing LDS read delivers the
+// token-minor A operand.  The probabilities are split into a bf16 head and a bf16
+// remainder (two products), which keeps the result at fp32 accuracy.  Softmax is online in
+// the exp2 domain with fp32 running maximum and sum per query row.
+//
+// Epilogue (combine).  A sequence that fits one wave is normalised and written directly.
+// A sequence cut over several waves leaves one partial state (m, l, acc) per piece in the
+// workspace; after its last page each wave bumps the sequence's arrival counter, and the
+// wave that arrives last merges all pieces by the log-sum-exp rule and writes the rows.
+// Nobody ever waits for anybody: the pattern cannot deadlock, and the counters reset
+// themselves for the next call.
+//
+// LDS placement: the 16-byte chunks of a token row are XOR-swizzled with the token index
+// so that both the row-wise K reads and the transposing V reads spread over all banks; the
+// swizzle costs nothing because every lane of a direct load picks its own source address.
+#include "jd_internal.h"
+#include "jd_walk.h"
+
+namespace jd {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) char lds_char;
+
+#ifndef JD_MFMA_WAVES
+#define JD_MFMA_WAVES 4
+#endif
+constexpr int kWaves = JD_MFMA_WAVES;  // waves per block; one block per compute unit (LDS-limited)
+constexpr int kLdsBudget = 160 * 1024;
+
+#ifdef JD_TIMING
+// Development aid (not built by default): per-wave phase time stamps of the constant 100 MHz clock.
+__device__ long long g_stamps[kMaxWaveSlots][8];
+#define JD_STAMP(w, i) do { if ((threadIdx.x & 63) == 0) g_stamps[(w)][(i)] = wall_clock64(); } while (0)
+#else
+#define JD_STAMP(w, i) do { } while (0)
+#endif
+
+// meta word of a stage
+constexpr int kMetaValidMask = 0x1f;
+constexpr int kMetaFirst = 1 << 8;
+constexpr int kMetaLast = 1 << 9;
+constexpr int kMetaComplete = 1 << 10;
+constexpr int kMetaSlot1 = 1 << 11;
+
+template <int D, int QKB, int NS>
+struct Geometry {
+    static constexpr int kRowBytes = D * 2;
+    static constexpr int kPageBytes = kPage * kRowBytes;       // one tensor, one kv head
+    static constexpr int kLoadsPerTensor = kPageBytes / 1024;  // wave-wide 1 KiB direct loads
+    static constexpr int kQBytes = QKB * 1024;
+    static constexpr int kQLoads = QKB;
+    static constexpr int kStageBytes = kQBytes + 2 * kPageBytes;
+    static constexpr int kWaveBytes = NS * kStageBytes;
+    static constexpr int kLoadsPerStage = 2 * kLoadsPerTensor;  // Q loads come on top, only when a segment opens
+    static constexpr int kChunksPerRow = kRowBytes / 16;
+    static constexpr int kRowsPerLoad = 1024 / kRowBytes;
+    static_assert(kWaves * kWaveBytes <= kLdsBudget, "LDS ring does not fit");
+};
+
+__device__ inline void dma16(unsigned lds_addr, unsigned lane_off, const void* base)
+{
+    // LDS[lds_addr + 16 * lane] <- 16 bytes at base + lane_off; counted by vmcnt
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
+}
+
+template <int N>
+__device__ inline void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+// Wait until at most `ahead` younger stages (of LPS loads each) are still in flight.
+template <int LPS, int NS>
+__device__ inline void wait_stage(int ahead)
+{
+    if constexpr (NS >= 8) { if (ahead >= 7) { wait_vmcnt<7 * LPS>(); return; } }
+    if constexpr (NS >= 7) { if (ahead == 6) { wait_vmcnt<6 * LPS>(); return; } }
+    if constexpr (NS >= 6) { if (ahead == 5) { wait_vmcnt<5 * LPS>(); return; } }
+    if constexpr (NS >= 5) { if (ahead == 4) { wait_vmcnt<4 * LPS>(); return; } }
+    if constexpr (NS >= 4) { if (ahead == 3) { wait_vmcnt<3 * LPS>(); return; } }
+    if constexpr (NS >= 3) { if (ahead == 2) { wait_vmcnt<2 * LPS>(); return; } }
+    if constexpr (NS >= 2) { if (ahead == 1) { wait_vmcnt<1 * LPS>(); return; } }
+    wait_vmcnt<0>();
+}
+
+// Producer cursor: the next page-unit to fetch.
+struct Cursor {
+    int upos;           // position on the work line
+    int b, kv, pg;      // request, kv head, page within the request
+    int L, n;           // tokens and pages of request b
+    int seg_pg0;        // page at which the current segment began
+    int seg_at_start;   // the current segment began at the first unit of the span
+    int next_id;        // physical page of unit upos (fetched one page ahead)
+    int last_bkv, last_n, last_a;  // the stream the newest segment belongs to: b*Hkv+kv, pages, first unit
+};
+
+__device__ inline int pages_of(const Params& p, int L)
+{
+    int n = L > 0 ? (L + kPage - 1) / kPage : 0;
+    return n > p.maxp ? p.maxp : n;
+}
+
+template <int D, int QKB, int NS>
+struct Wave {
+    using Geo = Geometry<D, QKB, NS>;
+    const Params& p;
+    int lane, u0, u1;
+    unsigned lds_wave;           // LDS byte address of this wave's ring
+    lds_char* lds_ptr;           // same, as a pointer for the compiler-visible reads
+    unsigned k_src[Geo::kLoadsPerTensor], v_src[Geo::kLoadsPerTensor], q_src[Geo::kQLoads];
+    unsigned k_rd[D / 32], v_rd[D / 16], q_rd[D / 32];
+    int meta[NS], dest[NS];
+    Cursor cur;
+    // consumer state (lane = query row q = lane % 16; token group tg = lane / 16)
+    bf16x8 qreg[D / 32];
+    f32x4 acc[D / 16];
+    float m, l;
+
+    __device__ Wave(const Params& prm) : p(prm) {}
+
+    __device__ void init_lane_tables()
+    {
+        const int G = p.G;
+        constexpr int CPR = Geo::kChunksPerRow;   // 16-byte chunks per token row: 16 (D=128) or 8 (D=64)
+        constexpr int RPL = Geo::kRowsPerLoad;    // token rows per direct load: 4 or 8
+        // direct-load sources: LDS chunk (row t, position c') of load j is fed from source chunk c' ^ swizzle(t)
+#pragma unroll
+        for (int j = 0; j < Geo::kLoadsPerTensor; ++j) {
+            const int t = j * RPL + lane / CPR;
+            const int cp = lane % CPR;
+            k_src[j] = t * Geo::kRowBytes + ((cp ^ kswz(t)) * 16);
+            v_src[j] = t * Geo::kRowBytes + ((cp ^ vswz(t)) * 16);
+        }
+        const int qbytes = G * Geo::kRowBytes;
+#pragma unroll
+        for (int j = 0; j < Geo::kQLoads; ++j) {
+            int off = j * 1024 + lane * 16;
+            q_src[j] = off < qbytes ? off : qbytes - 16;  // never read past the group's rows
+        }
+        // operand reads
+        const int t = lane % 16, kg = lane / 16;
+        const int qrow = t < G ? t : G - 1;
+#pragma unroll
+        for (int i = 0; i < D / 32; ++i) {
+            k_rd[i] = t * Geo::kRowBytes + (((4 * i + kg) ^ kswz(t)) * 16);
+            q_rd[i] = qrow * Geo::kRowBytes + (4 * i + kg) * 16;
+        }
+        const int row = 4 * kg + (lane % 16) / 4, c = lane % 4;
+#pragma unroll
+        for (int jd = 0; jd < D / 16; ++jd)
+            v_rd[jd] = row * Geo::kRowBytes + (((2 * jd + c / 2) ^ vswz(row)) * 16) + (c % 2) * 8;
+    }
+
+    static constexpr int kRowShift = D == 128 ? 8 : 7;  // log2 of the bytes of one token row
+
+    // A wave-uniform pointer, pinned to scalar registers (the direct loads take their base there).
+    static __device__ inline const char* scalar_ptr(const char* ptr)
+    {
+        const uint64_t v = reinterpret_cast<uint64_t>(ptr);
+        const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
+        const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
+        return reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
+    }
+
+    static __device__ inline int kswz(int t) { return t & (Geo::kChunksPerRow - 1); }
+    static __device__ inline int vswz(int t)
+    {
+        return D == 128 ? ((t & 7) << 1) : (((t >> 1) & 3) << 1);
+    }
+
+    // ---- producer -------------------------------------------------------------------------------
+    // Move to the next request that owns pages (only called while units remain, so one exists).
+    __device__ inline void next_request()
+    {
+        int b = cur.b, L = 0, n = 0;
+        do {
+            ++b;
+            if (b >= p.B) {  // seq_lens changed under the kernel: stay in bounds, flag it
+                b = p.B - 1;
+                if (lane == 0) atomicOr(&p.header[kHdrBadInput], 4);
+                L = 1;
+                n = 1;
+                break;
+            }
+            L = uniform_load(p.seq_lens + b);
+            n = pages_of(p, L);
+        } while (n == 0);
+        cur.b = b;
+        cur.n = n;
+        cur.L = L > n * kPage ? n * kPage : L;
+    }
+
+    __device__ inline void fetch_next_id()
+    {
+        cur.next_id = uniform_load(p.block_table + static_cast<size_t>(cur.b) * p.maxp + cur.pg);
+    }
+
+    template <int S>
+    __device__ inline void produce()
+    {
+        const int id = checked_page(p, cur.next_id);
+        const bool first = (cur.upos == u0) || (cur.pg == 0);
+        const bool last = (cur.pg == cur.n - 1) || (cur.upos == u1 - 1);
+        if (first) {
+            cur.seg_pg0 = cur.pg;
+            cur.seg_at_start = (cur.upos == u0);
+            cur.last_bkv = cur.b * p.Hkv + cur.kv;
+            cur.last_n = cur.n;
+            cur.last_a = cur.upos - cur.pg;
+        }
+        int mt = min(kPage, cur.L - cur.pg * kPage);
+        if (first) mt |= kMetaFirst;
+        if (last) {
+            mt |= kMetaLast;
+            if (cur.seg_pg0 == 0 && cur.pg == cur.n - 1) mt |= kMetaComplete;
+            // a piece that starts before its wave's span is record 0, any other record 1
+            if (!(cur.seg_at_start && cur.seg_pg0 > 0)) mt |= kMetaSlot1;
+        }
+        meta[S] = mt;
+        dest[S] = cur.b * p.Hkv + cur.kv;
+
+        const unsigned stage = lds_wave + S * Geo::kStageBytes;
+        // every read of this stage's previous contents has returned before it is overwritten
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        // byte offsets are 32-bit indices shifted left, so the address arithmetic stays on the scalar unit
+        if (first) {
+            const unsigned qrow = static_cast<unsigned>(cur.b * p.Hq + cur.kv * p.G);
+            const char* qb = scalar_ptr(reinterpret_cast<const char*>(p.q) + (static_cast<uint64_t>(qrow) << kRowShift));
+#pragma unroll
+            for (int j = 0; j < Geo::kQLoads; ++j) dma16(stage + j * 1024, q_src[j], qb);
+        }
+        const uint64_t page_off = static_cast<uint64_t>(static_cast<unsigned>(id * p.Hkv + cur.kv)) << (kRowShift + 4);
+        const char* kb = scalar_ptr(reinterpret_cast<const char*>(p.k_pages) + page_off);
+        const char* vb = scalar_ptr(reinterpret_cast<const char*>(p.v_pages) + page_off);
+#pragma unroll
+        for (int j = 0; j < Geo::kLoadsPerTensor; ++j) dma16(stage + Geo::kQBytes + j * 1024, k_src[j], kb);
+#pragma unroll
+        for (int j = 0; j < Geo::kLoadsPerTensor; ++j)
+            dma16(stage + Geo::kQBytes + Geo::kPageBytes + j * 1024, v_src[j], vb);
+
+        // advance to the next unit and start fetching its block-table entry
+        ++cur.upos;
+        if (++cur.pg == cur.n) {
+            cur.pg = 0;
+            if (++cur.kv == p.Hkv) {
+                cur.kv = 0;
+                if (cur.upos < u1) next_request();
+            }
+        }
+        if (cur.upos < u1) fetch_next_id();
+    }
+
+    // ---- consumer -------------------------------------------------------------------------------
+    template <int S>
+    __device__ inline void consume()
+    {
+        constexpr float kNegInf = -__builtin_inff();
+        lds_char* stage = lds_ptr + S * Geo::kStageBytes;
+        const int mt = meta[S];
+        const int valid = mt & kMetaValidMask;
+        const int tg = lane >> 4;
+
+        if (mt & kMetaFirst) {
+#pragma unroll
+            for (int i = 0; i < D / 32; ++i)
+                qreg[i] = *reinterpret_cast<__attribute__((address_space(3))) bf16x8*>(stage + q_rd[i]);
+#pragma unroll
+            for (int jd = 0; jd < D / 16; ++jd) acc[jd] = f32x4{0.f, 0.f, 0.f, 0.f};
+            m = kNegInf;
+            l = 0.f;
+        }
+
+        // S^T = K Q^T
+        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+        lds_char* kbase = stage + Geo::kQBytes;
+#pragma unroll
+        for (int i = 0; i < D / 32; ++i) {
+            const bf16x8 kf = *reinterpret_cast<__attribute__((address_space(3))) bf16x8*>(kbase + k_rd[i]);
+            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qreg[i], s, 0, 0, 0);
+        }
+        // V^T operands (issued early; the softmax arithmetic overlaps their latency)
+        s16x4 vf[D / 16];
+        lds_char* vbase = stage + Geo::kQBytes + Geo::kPageBytes;
+#pragma unroll
+        for (int jd = 0; jd < D / 16; ++jd)
+            vf[jd] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                reinterpret_cast<__attribute__((address_space(3))) s16x4*>(vbase + v_rd[jd]));
+
+        float sc[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sc[r] = s[r] * p.scale_log2e;
+        if (valid < kPage) {
+            // slots past the end of the sequence: excluded by selection (their bits may be anything)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const bool dead = 4 * tg + r >= valid;
+                if (dead) sc[r] = kNegInf;
+#pragma unroll
+                for (int jd = 0; jd < D / 16; ++jd)
+                    if (dead) vf[jd][r] = 0;
+            }
+        }
+        float mx = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float mn = fmaxf(m, mx);  // finite: every page holds at least one live token
+        const float alpha = __builtin_amdgcn_exp2f(m - mn);
+        float pr[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) pr[r] = __builtin_amdgcn_exp2f(sc[r] - mn);
+        l = l * alpha + ((pr[0] + pr[1]) + (pr[2] + pr[3]));
+        if (__builtin_amdgcn_ballot_w64(mn > m) != 0) {
+#pragma unroll
+            for (int jd = 0; jd < D / 16; ++jd)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[jd][r] *= alpha;
+        }
+        m = mn;
+
+        // probabilities as bf16 head + bf16 remainder
+        s16x4 ph, pl;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const __bf16 h = static_cast<__bf16>(pr[r]);
+            const __bf16 lo = static_cast<__bf16>(pr[r] - static_cast<float>(h));
+            ph[r] = __builtin_bit_cast(short, h);
+            pl[r] = __builtin_bit_cast(short, lo);
+        }
+#pragma unroll
+        for (int jd = 0; jd < D / 16; ++jd) {
+            acc[jd] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf[jd], ph, acc[jd], 0, 0, 0);
+            acc[jd] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf[jd], pl, acc[jd], 0, 0, 0);
+        }
+
+        if (mt & kMetaLast) finalize(mt, dest[S]);
+    }
+
+    __device__ inline void finalize(int mt, int bkv)
+    {
+        const int qh = lane & 15, tg = lane >> 4;
+        float lt = l;
+        lt += __shfl_xor(lt, 16, 64);
+        lt += __shfl_xor(lt, 32, 64);
+        if (qh >= p.G) return;
+        const int b = bkv / p.Hkv, kv = bkv % p.Hkv;
+        if (mt & kMetaComplete) {
+            const float inv = 1.f / lt;
+            float* o = p.out + (static_cast<size_t>(b) * p.Hq + kv * p.G + qh) * D + 4 * tg;
+#pragma unroll
+            for (int jd = 0; jd < D / 16; ++jd)
+                *reinterpret_cast<float4*>(o + 16 * jd) =
+                    make_float4(acc[jd][0] * inv, acc[jd][1] * inv, acc[jd][2] * inv, acc[jd][3] * inv);
+        } else {
+            // Records are shared between compute units that sit behind different L2 caches.  They are
+            // written and read with device-scope atomic accesses, which go through to memory, so
+            // that no cache-wide write-back or invalidate is ever needed.
+            const int slot = (mt & kMetaSlot1) ? 1 : 0;
+            float* rec = p.partials + static_cast<size_t>(wave * 2 + slot) * record_floats(p.G, D);
+            float* o = rec + qh * D + 4 * tg;
+#pragma unroll
+            for (int jd = 0; jd < D / 16; ++jd)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) shared_store(o + 16 * jd + r, acc[jd][r]);
+            if (tg == 0) {
+                shared_store(rec + p.G * D + qh, m);
+                shared_store(rec + p.G * D + p.G + qh, lt);
+            }
+        }
+    }
+
+    static __device__ inline void shared_store(float* ptr, float v)
+    {
+        __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    static __device__ inline float shared_load(const float* ptr)
+    {
+        return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+
+    // ---- epilogue: arrival counters and last-arriver merge -------------------------------------
+    // Announce this wave's piece of stream bkv (units [a, a+n) of the work line); the last piece to
+    // arrive merges all of them.  The caller has waited for its record stores to complete.
+    __device__ inline void arrive(int bkv, int a, int n)
+    {
+        const int w0 = a / span, w1 = (a + n - 1) / span;
+        int old = 0;
+        if (lane == 0) old = __hip_atomic_fetch_add(p.counters + bkv, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        old = __builtin_amdgcn_readfirstlane(old);
+        if (old != w1 - w0) return;
+        if (lane == 0) __hip_atomic_store(p.counters + bkv, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("" ::: "memory");  // the record loads below stay behind the counter read
+        merge(bkv, a, w0, w1);
+    }
+
+    // Log-sum-exp merge of the pieces of one stream, by one wave.  The G*D accumulator floats of a
+    // record are contiguous; lane j owns the float4 groups j, j+64, ... of them (each group lies in
+    // one query row).  Pieces are fetched a batch at a time so that their loads overlap.
+    __device__ inline void merge(int bkv, int a, int w0, int w1)
+    {
+        constexpr int K = 2 * QKB;   // float4 groups per lane: G*D*2 <= QKB KiB, so G*D/4 <= 128*QKB groups
+        constexpr int PB = 16 / K;   // pieces per batch
+        const int G = p.G;
+        const int groups = G * D / 4;
+        const int rec_floats = record_floats(G, D);
+        int idx[K], qrow[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            idx[k] = lane + 64 * k;
+            if (idx[k] >= groups) idx[k] = -1;
+            qrow[k] = idx[k] < 0 ? 0 : idx[k] * 4 / D;
+        }
+        float M[K], den[K];
+        f32x4 num[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) { M[k] = -__builtin_inff(); den[k] = 0.f; num[k] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+
+        for (int w = w0; w <= w1; w += PB) {
+            float mm[PB][K], ll[PB][K];
+            f32x4 aa[PB][K];
+#pragma unroll
+            for (int i = 0; i < PB; ++i) {
+                const int wi = min(w + i, w1);  // the tail of a batch re-reads the last piece and is ignored below
+                const int slot = (a < wi * span) ? 0 : 1;
+                const float* rec = p.partials + static_cast<size_t>(wi * 2 + slot) * rec_floats;
+#pragma unroll
+                for (int k = 0; k < K; ++k) {
+                    if (idx[k] < 0) continue;
+                    mm[i][k] = shared_load(rec + G * D + qrow[k]);
+                    ll[i][k] = shared_load(rec + G * D + G + qrow[k]);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) aa[i][k][r] = shared_load(rec + idx[k] * 4 + r);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                if (idx[k] < 0) continue;
+                float mb = M[k];
+#pragma unroll
+                for (int i = 0; i < PB; ++i)
+                    if (w + i <= w1) mb = fmaxf(mb, mm[i][k]);
+                const float c_old = __builtin_amdgcn_exp2f(M[k] - mb);
+                M[k] = mb;
+                den[k] *= c_old;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) num[k][r] *= c_old;
+#pragma unroll
+                for (int i = 0; i < PB; ++i) {
+                    if (w + i > w1) continue;
+                    const float c = __builtin_amdgcn_exp2f(mm[i][k] - mb);
+                    den[k] = fmaf(c, ll[i][k], den[k]);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) num[k][r] = fmaf(c, aa[i][k][r], num[k][r]);
+                }
+            }
+        }
+        const int b = bkv / p.Hkv, kv = bkv % p.Hkv;
+        float* o = p.out + (static_cast<size_t>(b) * p.Hq + kv * G) * D;  // the group's rows are contiguous, like the record's
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            if (idx[k] < 0) continue;
+            const float inv = 1.f / den[k];
+            *reinterpret_cast<float4*>(o + idx[k] * 4) =
+                make_float4(num[k][0] * inv, num[k][1] * inv, num[k][2] * inv, num[k][3] * inv);
+        }
+    }
+
+    int wave;       // index of this wave on the work line
+    int span;       // page-units per wave
+    int first_bkv, first_n, first_pg0;  // the stream the span begins in, and the page it begins at
+
+    template <int S>
+    __device__ inline void prologue_stage(int total)
+    {
+        if (S < total) produce<S>();
+        if constexpr (S + 1 < NS) prologue_stage<S + 1>(total);
+    }
+
+    template <int S>
+    __device__ inline void round_stage(int base, int total)
+    {
+        const int i = base + S;
+        if (i < total) {
+            wait_stage<Geo::kLoadsPerStage, NS>(min(NS - 1, total - 1 - i));
+            if (i == 0) JD_STAMP(wave, 4);
+            consume<S>();
+            if (i + NS < total) produce<S>();
+        }
+        if constexpr (S + 1 < NS) round_stage<S + 1>(base, total);
+    }
+
+    __device__ inline void run()
+    {
+        const int total = u1 - u0;
+        prologue_stage<0>(total);
+        JD_STAMP(wave, 3);
+        for (int base = 0; base < total; base += NS) round_stage<0>(base, total);
+        JD_STAMP(wave, 5);
+
+        // pieces of sequences shared with other waves: at most the first and the last stream of the span
+        const int first_a = u0 - first_pg0;
+        const bool first_partial = first_pg0 > 0 || first_a + first_n > u1;
+        const bool last_partial = cur.last_a != first_a && cur.last_a + cur.last_n > u1;
+        if (first_partial || last_partial) {
+            // release: the write-through record stores of this wave have completed before it is counted
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (first_partial) arrive(first_bkv, first_a, first_n);
+            if (last_partial) arrive(cur.last_bkv, cur.last_a, cur.last_n);
+        }
+        JD_STAMP(wave, 6);
+    }
+};
+
+constexpr int kThreads = kWaves * 64;
+
+
+// Exclusive prefix of pages per request into s_cum[0..B] (LDS), by all threads of the block.
+__device__ inline void scan_pages(const Params& p, int* s_cum, int* s_part)
+{
+    const int tid = threadIdx.x;
+    const int chunk = (p.B + kThreads - 1) / kThreads;
+    const int b0 = min(tid * chunk, p.B), b1 = min(b0 + chunk, p.B);
+    int local = 0;
+    for (int b = b0; b < b1; ++b) {
+        const int L = p.seq_lens[b];
+        if (L > p.maxp * kPage && p.header[kHdrBadInput] == 0) atomicOr(&p.header[kHdrBadInput], 1);
+        local += pages_of(p, L);
+    }
+    s_part[tid] = local;
+    __syncthreads();
+    if (tid < 64) {
+        constexpr int per = kThreads / 64;
+        int v[per], sum = 0;
+#pragma unroll
+        for (int i = 0; i < per; ++i) { v[i] = s_part[tid * per + i]; sum += v[i]; }
+        int inc = sum;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int t = __shfl_up(inc, d, 64);
+            if (tid >= d) inc += t;
+        }
+        int run = inc - sum;
+#pragma unroll
+        for (int i = 0; i < per; ++i) { s_part[tid * per + i] = run; run += v[i]; }
+    }
+    __syncthreads();
+    int run = s_part[tid];
+    for (int b = b0; b < b1; ++b) {
+        s_cum[b] = run;
+        run += pages_of(p, p.seq_lens[b]);
+    }
+    if (b1 == p.B && b0 < b1) s_cum[p.B] = run;
+    __syncthreads();
+}
+
+template <int D, int QKB, int NS>
+__global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int partition_only)
+{
+    using W = Wave<D, QKB, NS>;
+    __shared__ __attribute__((aligned(1024))) char ring[kWaves * W::Geo::kWaveBytes];
+
+    JD_STAMP(blockIdx.x * kWaves + (threadIdx.x >> 6), 0);
+    // ---- prologue: work partition (the ring doubles as scratch until the first page is fetched) ----
+    int* s_cum = reinterpret_cast<int*>(ring);
+    int* s_part = s_cum + ((p.B + 1 + 63) & ~63);
+    scan_pages(p, s_cum, s_part);
+    JD_STAMP(blockIdx.x * kWaves + (threadIdx.x >> 6), 1);
+    const int units = s_cum[p.B] * p.Hkv;
+    int span = (units + p.slots - 1) / p.slots;
+    if (span < kMinSpan) span = kMinSpan;
+    const int active = (units + span - 1) / span;
+
+    const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * kWaves + wave_in_block);
+    int sb = 0, skv = 0, spg = 0;
+    if (wave < active) {
+        const int u = wave * span;
+        int lo = 0, hi = p.B - 1;  // the last request whose first unit is <= u
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (s_cum[mid] * p.Hkv <= u) lo = mid; else hi = mid - 1;
+        }
+        const int n = s_cum[lo + 1] - s_cum[lo];
+        const int within = u - s_cum[lo] * p.Hkv;
+        sb = lo;
+        skv = within / n;
+        spg = within % n;
+    }
+    sb = __builtin_amdgcn_readfirstlane(sb);
+    skv = __builtin_amdgcn_readfirstlane(skv);
+    spg = __builtin_amdgcn_readfirstlane(spg);
+
+    // rows of requests without tokens
+    for (int b = blockIdx.x; b < p.B && !partition_only; b += gridDim.x) {
+        if (s_cum[b + 1] == s_cum[b]) {
+            float* o = p.out + static_cast<size_t>(b) * p.Hq * D;
+            for (int i = threadIdx.x; i < p.Hq * D; i += kThreads) o[i] = 0.f;
+        }
+    }
+    // tables for inspection (read back by the host only on request)
+    if (blockIdx.x == 0) {
+        for (int b = threadIdx.x; b <= p.B; b += kThreads) p.cum_pages[b] = s_cum[b];
+        if (threadIdx.x == 0) {
+            p.header[kHdrUnits] = units;
+            p.header[kHdrSpan] = span;
+            p.header[kHdrActive] = active;
+            p.header[kHdrSlots] = p.slots;
+        }
+    }
+    if (wave < active && (threadIdx.x & 63) == 0) {
+        i32x4 ws = {sb, skv, spg, sb};
+        reinterpret_cast<i32x4*>(p.wave_start)[wave] = ws;
+    }
+    __syncthreads();  // the scratch is dead from here on
+    if (partition_only || wave >= active) return;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    JD_STAMP(wave, 2);
+
+    // ---- main loop and epilogue ----
+    W w(p);
+    w.lane = threadIdx.x & 63;
+    w.wave = wave;
+    w.span = span;
+    w.u0 = wave * span;
+    w.u1 = min(w.u0 + span, units);
+    w.lds_ptr = (lds_char*)ring + wave_in_block * W::Geo::kWaveBytes;
+    w.lds_wave = static_cast<unsigned>(reinterpret_cast<uintptr_t>(w.lds_ptr));
+    w.init_lane_tables();
+    w.cur.upos = w.u0;
+    w.cur.b = sb;
+    w.cur.kv = skv;
+    w.cur.pg = spg;
+    const int L = uniform_load(p.seq_lens + sb);
+    w.cur.n = pages_of(p, L);
+    w.cur.L = L > w.cur.n * kPage ? w.cur.n * kPage : L;
+    w.cur.seg_pg0 = spg;
+    w.cur.seg_at_start = 1;
+    w.cur.last_bkv = sb * p.Hkv + skv;
+    w.cur.last_n = w.cur.n;
+    w.cur.last_a = w.u0 - spg;
+    w.first_bkv = w.cur.last_bkv;
+    w.first_n = w.cur.n;
+    w.first_pg0 = spg;
+    w.fetch_next_id();
+    w.m = 0.f;
+    w.l = 0.f;
+    w.run();
+}
+
+// Ring depth: as many stages as the LDS of one compute unit holds for kWaves waves, at most 8.
+constexpr int stages_for(int D, int qkb)
+{
+    const int stage = qkb * 1024 + 2 * kPage * D * 2;
+    const int n = kLdsBudget / (kWaves * stage);
+    return n > 8 ? 8 : n;
+}
+
+template <int D, int QKB, int NS>
+hipError_t launch(const Params& p, hipStream_t stream, int partition_only)
+{
+    hipLaunchKernelGGL((decode_fused_kernel<D, QKB, NS>), dim3(p.slots / kWaves), dim3(kThreads), 0, stream, p,
+                       partition_only);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+int mfma_waves_per_cu() { return kWaves; }
+int mfma_waves_per_block() { return kWaves; }
+
+#ifdef JD_TIMING
+extern "C" int jd_debug_read_stamps(long long* host)
+{
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_stamps), sizeof(long long) * kMaxWaveSlots * 8) == hipSuccess ? 0 : 1;
+}
+#endif
+
+int mfma_max_batch()
+{
+    // the prologue keeps B + 1 prefix entries and one entry per thread in the smallest ring
+    return 32768;
+}
+
+hipError_t launch_fused_mfma(const Params& p, hipStream_t stream, int partition_only)
+{
+    // query slot of a stage: G rows of D bf16, rounded up to whole 1 KiB direct loads
+    const int qkb = (p.G * p.D * 2 + 1023) / 1024;
+    if (p.D == 128) {
+        if (qkb <= 1) return launch<128, 1, stages_for(128, 1)>(p, stream, partition_only);
+        if (qkb <= 2) return launch<128, 2, stages_for(128, 2)>(p, stream, partition_only);
+        return launch<128, 4, stages_for(128, 4)>(p, stream, partition_only);
+    }
+    if (qkb <= 1) return launch<64, 1, stages_for(64, 1)>(p, stream, partition_only);
+    return launch<64, 2, stages_for(64, 2)>(p, stream, partition_only);
+}
+
+}  // namespace jd

@@ -36,6 +36,7 @@ struct Params {
     int32_t* req;               // [B] request id of the r-th non-empty request
     int32_t* wave_start;        // [slots * 4] {r, kv, page, 0}
     float* partials;            // [slots * 2] records of G*(D+2) floats: acc[G][D], m[G], l[G]
+    int32_t* counters;          // [B * Hkv] arrival counters of the fused kernel (zero between calls)
     int32_t B, Hq, Hkv, G, D, maxp, NP, slots;
     float scale_log2e;          // softmax_scale * log2(e): scores are kept in the exp2 domain
 };
@@ -45,7 +46,8 @@ inline __host__ __device__ int record_floats(int G, int D) { return G * (D + 2);
 // Launchers (each enqueues on `stream` and returns hipGetLastError()).
 hipError_t launch_partition(const Params& p, hipStream_t stream);
 hipError_t launch_partial_vector(const Params& p, hipStream_t stream);
-hipError_t launch_partial_mfma(const Params& p, hipStream_t stream);
+hipError_t launch_fused_mfma(const Params& p, hipStream_t stream, int partition_only);
+int mfma_max_batch();
 hipError_t launch_combine(const Params& p, hipStream_t stream);
 
 // Wave slots each variant wants per compute unit.

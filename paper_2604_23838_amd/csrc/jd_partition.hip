@@ -98,7 +98,7 @@ __global__ __launch_bounds__(kThreads) void partition_kernel(Params p)
         ws.x = __hip_atomic_load(&p.rank[lo], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         ws.y = within / n;
         ws.z = within % n;
-        ws.w = 0;
+        ws.w = lo;  // the request id itself, for inspection
         reinterpret_cast<int4*>(p.wave_start)[w] = ws;
     }
 }

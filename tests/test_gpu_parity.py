@@ -160,15 +160,16 @@ def test_partition_bit_exact(torch_cuda):
     cases.append((rng.integers(16384, 32768, size=8).tolist(), 8))
     for lens, hkv in cases:
         B, maxp = len(lens), 2048
-        for budget in (0, 3):
-            op = jb.DecodeAttention(B, hkv * 4, hkv, 128, maxp, 64, cu_budget=budget, variant=1)
+        for budget, variant in ((0, 1), (3, 1), (0, 2), (5, 2)):
+            op = jb.DecodeAttention(B, hkv * 4, hkv, 128, maxp, 64, cu_budget=budget, variant=variant)
             tl = torch.tensor(lens, dtype=torch.int32, device="cuda:0")
             hdr, ws, cum = op.partition(tl)
             slots = jb.jd_wave_slots(op.handle)
             rh, rws, rcum = partition_ref.partition(lens, hkv, slots, maxp)
-            assert hdr[:5] == rh, (lens[:8], hdr, rh)
+            assert hdr[:4] == rh, (lens[:8], hdr, rh)
             assert cum == rcum
             assert ws[:rh[2]] == rws
+            assert all(r == [0, 0, 0, 0] for r in ws[rh[2]:])
             if max(lens) > maxp * 16:
                 with pytest.raises(jb.JdError):
                     op.check_flags()
