@@ -131,16 +131,23 @@ jd_status jd_debug_partition(jd_handle *h, const int32_t *seq_lens, int32_t *hea
                              int32_t *wave_start_host, int32_t *cum_pages_host, void *stream);
 
 /*
+ * The schedule for a work line of `units` page-units and `wave_slots` waves, as the kernels compute
+ * it: out = {span, active_waves} (see jd_debug_partition).  Pure host function.
+ */
+jd_status jd_debug_schedule(int32_t units, int32_t wave_slots, int32_t out[2]);
+
+/*
  * Per-kernel timing with HIP events, for benchmarks.  jd_profile_enable creates 4 * max_calls
- * events (max_calls = 0 frees them and switches timing off); while enabled, each of the next
- * max_calls jd_decode_attention calls records an event before and after each of its three
- * kernels on the call's stream (do not capture such calls into a graph).  jd_profile_read
- * synchronises on the last recorded event, stores the summed durations in milliseconds of
- * {work partition, split-KV partial pass, combine} and the number of calls summed, and
- * restarts the recording window.  The matrix-core variant runs all three phases in one fused
+ * events (max_calls = 0 frees them and switches timing off); while enabled, every `every`-th
+ * jd_decode_attention call (the first one included), up to max_calls of them, records an event
+ * before and after each of its three kernels on the call's stream (do not capture such calls into
+ * a graph; an event record costs a few microseconds of stream time, hence the sampling).
+ * jd_profile_read synchronises on the last recorded event, stores the summed durations in
+ * milliseconds of {work partition, split-KV partial pass, combine} and the number of calls summed,
+ * and restarts the recording window.  The matrix-core variant runs all three phases in one fused
  * kernel: its whole duration is reported under the partial pass, the other two read 0.
  */
-jd_status jd_profile_enable(jd_handle *h, int32_t max_calls);
+jd_status jd_profile_enable(jd_handle *h, int32_t max_calls, int32_t every);
 jd_status jd_profile_read(jd_handle *h, float ms_sum[3], int32_t *calls);
 
 /*

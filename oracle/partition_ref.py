@@ -19,6 +19,12 @@ def pages(L: int, max_pages: int) -> int:
     return min(n, max_pages)
 
 
+def schedule(units: int, slots: int, min_span: int = 4):
+    """(span, active_waves) for a work line of `units` page-units."""
+    span = max(min_span, -(-units // slots))
+    return span, -(-units // span)
+
+
 def partition(seq_lens, num_kv_heads: int, slots: int, max_pages: int, min_span: int = 4):
     """Returns (header, wave_start, cum_pages) as the library reports them:
     header = [units, span, active_waves, slots];

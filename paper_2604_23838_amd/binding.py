@@ -19,7 +19,7 @@ JD_VARIANT_DEFAULT, JD_VARIANT_VECTOR, JD_VARIANT_MFMA = range(3)
 EXPORTS = ("jd_validate_config", "jd_workspace_bytes", "jd_create", "jd_decode_attention",
            "jd_check_device_flags", "jd_debug_partition", "jd_profile_enable", "jd_profile_read",
            "jd_debug_stream_read", "jd_debug_stream_copy",
-           "jd_wave_slots", "jd_destroy",
+           "jd_debug_schedule", "jd_wave_slots", "jd_destroy",
            "jd_last_error_string")
 
 
@@ -60,7 +60,7 @@ def lib():
         l.jd_check_device_flags.restype = C.c_int
         l.jd_debug_partition.argtypes = [vp, vp, vp, vp, vp, vp]
         l.jd_debug_partition.restype = C.c_int
-        l.jd_profile_enable.argtypes = [vp, C.c_int32]
+        l.jd_profile_enable.argtypes = [vp, C.c_int32, C.c_int32]
         l.jd_profile_enable.restype = C.c_int
         l.jd_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
         l.jd_profile_read.restype = C.c_int
@@ -68,6 +68,8 @@ def lib():
         l.jd_debug_stream_read.restype = C.c_int
         l.jd_debug_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
         l.jd_debug_stream_copy.restype = C.c_int
+        l.jd_debug_schedule.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
+        l.jd_debug_schedule.restype = C.c_int
         l.jd_wave_slots.argtypes = [vp]
         l.jd_wave_slots.restype = C.c_int32
         l.jd_destroy.argtypes = [vp]
@@ -111,6 +113,15 @@ def jd_check_device_flags(handle, stream=0) -> None:
         raise JdError(st, jd_last_error_string(handle))
 
 
+def jd_debug_schedule(units: int, wave_slots: int):
+    """[span, active_waves] for a work line of `units` page-units."""
+    out = (C.c_int32 * 2)()
+    st = lib().jd_debug_schedule(units, wave_slots, out)
+    if st != JD_OK:
+        raise JdError(st, jd_last_error_string(None))
+    return list(out)
+
+
 def jd_wave_slots(handle) -> int:
     return int(lib().jd_wave_slots(handle))
 
@@ -129,8 +140,8 @@ def jd_debug_partition(handle, seq_lens, batch: int, stream=0):
     return list(hdr), [w[4 * i:4 * i + 4] for i in range(slots)], list(cum)
 
 
-def jd_profile_enable(handle, max_calls: int) -> None:
-    st = lib().jd_profile_enable(handle, max_calls)
+def jd_profile_enable(handle, max_calls: int, every: int = 1) -> None:
+    st = lib().jd_profile_enable(handle, max_calls, every)
     if st != JD_OK:
         raise JdError(st, jd_last_error_string(handle))
 

@@ -18,7 +18,7 @@ struct jd_handle {
     int variant;            // resolved: JD_VARIANT_VECTOR or JD_VARIANT_MFMA
     int device;
     std::vector<hipEvent_t> events;  // 4 per profiled call
-    int prof_max = 0, prof_calls = 0;
+    int prof_max = 0, prof_calls = 0, prof_every = 1, prof_seen = 0;
     std::string error;
 };
 
@@ -196,7 +196,7 @@ jd_status jd_decode_attention(jd_handle* h, const void* q, const void* k_pages, 
     p.seq_lens = seq_lens;
     p.out = out;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipEvent_t* ev = (h->prof_calls < h->prof_max) ? &h->events[4 * h->prof_calls] : nullptr;
+    hipEvent_t* ev = (h->prof_calls < h->prof_max && h->prof_seen++ % h->prof_every == 0) ? &h->events[4 * h->prof_calls] : nullptr;
     const bool fused = h->variant != JD_VARIANT_VECTOR;  // one launch does partition, partial pass and combine
     hipError_t e = ev ? hipEventRecord(ev[0], s) : hipSuccess;
     if (e == hipSuccess && !fused) e = jd::launch_partition(p, s);
@@ -260,10 +260,10 @@ jd_status jd_debug_partition(jd_handle* h, const int32_t* seq_lens, int32_t* hea
     return JD_OK;
 }
 
-jd_status jd_profile_enable(jd_handle* h, int32_t max_calls)
+jd_status jd_profile_enable(jd_handle* h, int32_t max_calls, int32_t every)
 {
     if (!h) return fail(nullptr, JD_ERR_INVALID_ARG, "handle is NULL");
-    if (max_calls < 0 || max_calls > (1 << 20)) return fail(h, JD_ERR_INVALID_ARG, "max_calls out of range");
+    if (max_calls < 0 || max_calls > (1 << 20) || every < 1) return fail(h, JD_ERR_INVALID_ARG, "max_calls or every out of range");
     for (hipEvent_t ev : h->events) (void)hipEventDestroy(ev);
     h->events.clear();
     h->prof_max = h->prof_calls = 0;
@@ -278,6 +278,8 @@ jd_status jd_profile_enable(jd_handle* h, int32_t max_calls)
         h->events.push_back(ev);
     }
     h->prof_max = max_calls;
+    h->prof_every = every;
+    h->prof_seen = 0;
     return JD_OK;
 }
 
@@ -297,6 +299,14 @@ jd_status jd_profile_read(jd_handle* h, float ms_sum[3], int32_t* calls)
         }
     h->prof_calls = 0;
     if (e != hipSuccess) return fail(h, JD_ERR_HIP, std::string("reading event times failed: ") + hipGetErrorString(e));
+    return JD_OK;
+}
+
+jd_status jd_debug_schedule(int32_t units, int32_t wave_slots, int32_t out[2])
+{
+    if (units < 0 || wave_slots <= 0 || !out) return fail(nullptr, JD_ERR_INVALID_ARG, "units >= 0, wave_slots > 0 and out != NULL required");
+    out[0] = jd::span_for(units, wave_slots);
+    out[1] = (units + out[0] - 1) / out[0];
     return JD_OK;
 }
 

@@ -48,6 +48,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) char lds_char;
 
 #ifndef JD_MFMA_WAVES
@@ -120,8 +121,13 @@ struct Cursor {
     int L, n;           // tokens and pages of request b
     int seg_pg0;        // page at which the current segment began
     int seg_at_start;   // the current segment began at the first unit of the span
-    int next_id;        // physical page of unit upos (fetched one page ahead)
     int last_bkv, last_n, last_a;  // the stream the newest segment belongs to: b*Hkv+kv, pages, first unit
+};
+
+// One planned page-unit: everything issue() needs, with the block-table entry already on its way.
+struct Planned {
+    int meta, dest, id;
+    unsigned qrow;
 };
 
 __device__ inline int pages_of(const Params& p, int L)
@@ -141,6 +147,7 @@ struct Wave {
     unsigned k_rd[D / 32], v_rd[D / 16], q_rd[D / 32];
     int meta[NS], dest[NS];
     Cursor cur;
+    Planned nx;
     // consumer state (lane = query row q = lane % 16; token group tg = lane / 16)
     bf16x8 qreg[D / 32];
     f32x4 acc[D / 16];
@@ -220,15 +227,10 @@ struct Wave {
         cur.L = L > n * kPage ? n * kPage : L;
     }
 
-    __device__ inline void fetch_next_id()
+    // Describe the unit at the cursor, request its block-table entry, and move the cursor on.
+    __device__ inline void plan(Planned& r)
     {
-        cur.next_id = uniform_load(p.block_table + static_cast<size_t>(cur.b) * p.maxp + cur.pg);
-    }
-
-    template <int S>
-    __device__ inline void produce()
-    {
-        const int id = checked_page(p, cur.next_id);
+        r.id = uniform_load(p.block_table + static_cast<size_t>(cur.b) * p.maxp + cur.pg);
         const bool first = (cur.upos == u0) || (cur.pg == 0);
         const bool last = (cur.pg == cur.n - 1) || (cur.upos == u1 - 1);
         if (first) {
@@ -246,29 +248,10 @@ struct Wave {
             // a piece that starts before its wave's span is record 0, any other record 1
             if (!(cur.seg_at_start && cur.seg_pg0 > 0)) mt |= kMetaSlot1;
         }
-        meta[S] = mt;
-        dest[S] = cur.b * p.Hkv + cur.kv;
+        r.meta = mt;
+        r.dest = cur.b * p.Hkv + cur.kv;
+        r.qrow = static_cast<unsigned>(cur.b * p.Hq + cur.kv * p.G);
 
-        const unsigned stage = lds_wave + S * Geo::kStageBytes;
-        // every read of this stage's previous contents has returned before it is overwritten
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        // byte offsets are 32-bit indices shifted left, so the address arithmetic stays on the scalar unit
-        if (first) {
-            const unsigned qrow = static_cast<unsigned>(cur.b * p.Hq + cur.kv * p.G);
-            const char* qb = scalar_ptr(reinterpret_cast<const char*>(p.q) + (static_cast<uint64_t>(qrow) << kRowShift));
-#pragma unroll
-            for (int j = 0; j < Geo::kQLoads; ++j) dma16(stage + j * 1024, q_src[j], qb);
-        }
-        const uint64_t page_off = static_cast<uint64_t>(static_cast<unsigned>(id * p.Hkv + cur.kv)) << (kRowShift + 4);
-        const char* kb = scalar_ptr(reinterpret_cast<const char*>(p.k_pages) + page_off);
-        const char* vb = scalar_ptr(reinterpret_cast<const char*>(p.v_pages) + page_off);
-#pragma unroll
-        for (int j = 0; j < Geo::kLoadsPerTensor; ++j) dma16(stage + Geo::kQBytes + j * 1024, k_src[j], kb);
-#pragma unroll
-        for (int j = 0; j < Geo::kLoadsPerTensor; ++j)
-            dma16(stage + Geo::kQBytes + Geo::kPageBytes + j * 1024, v_src[j], vb);
-
-        // advance to the next unit and start fetching its block-table entry
         ++cur.upos;
         if (++cur.pg == cur.n) {
             cur.pg = 0;
@@ -277,7 +260,33 @@ struct Wave {
                 if (cur.upos < u1) next_request();
             }
         }
-        if (cur.upos < u1) fetch_next_id();
+    }
+
+    // Start the direct loads of a planned unit into stage S.
+    template <int S>
+    __device__ inline void issue(const Planned& r)
+    {
+        const int id = checked_page(p, r.id);
+        meta[S] = r.meta;
+        dest[S] = r.dest;
+        const int kv = r.dest % p.Hkv;
+        const unsigned stage = lds_wave + S * Geo::kStageBytes;
+        // every read of this stage's previous contents has returned before it is overwritten
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        // byte offsets are 32-bit indices shifted left, so the address arithmetic stays on the scalar unit
+        if (r.meta & kMetaFirst) {
+            const char* qb = scalar_ptr(reinterpret_cast<const char*>(p.q) + (static_cast<uint64_t>(r.qrow) << kRowShift));
+#pragma unroll
+            for (int j = 0; j < Geo::kQLoads; ++j) dma16(stage + j * 1024, q_src[j], qb);
+        }
+        const uint64_t page_off = static_cast<uint64_t>(static_cast<unsigned>(id * p.Hkv + kv)) << (kRowShift + 4);
+        const char* kb = scalar_ptr(reinterpret_cast<const char*>(p.k_pages) + page_off);
+        const char* vb = scalar_ptr(reinterpret_cast<const char*>(p.v_pages) + page_off);
+#pragma unroll
+        for (int j = 0; j < Geo::kLoadsPerTensor; ++j) dma16(stage + Geo::kQBytes + j * 1024, k_src[j], kb);
+#pragma unroll
+        for (int j = 0; j < Geo::kLoadsPerTensor; ++j)
+            dma16(stage + Geo::kQBytes + Geo::kPageBytes + j * 1024, v_src[j], vb);
     }
 
     // ---- consumer -------------------------------------------------------------------------------
@@ -385,26 +394,38 @@ struct Wave {
             // written and read with device-scope atomic accesses, which go through to memory, so
             // that no cache-wide write-back or invalidate is ever needed.
             const int slot = (mt & kMetaSlot1) ? 1 : 0;
-            float* rec = p.partials + static_cast<size_t>(wave * 2 + slot) * record_floats(p.G, D);
-            float* o = rec + qh * D + 4 * tg;
+            const unsigned rec = static_cast<unsigned>(wave * 2 + slot) * record_floats(p.G, D) * 4u;  // byte offset
+            const unsigned o = rec + (qh * D + 4 * tg) * 4u;
 #pragma unroll
-            for (int jd = 0; jd < D / 16; ++jd)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) shared_store(o + 16 * jd + r, acc[jd][r]);
+            for (int jd = 0; jd < D / 16; ++jd) shared_store4(o + 64 * jd, acc[jd]);
             if (tg == 0) {
-                shared_store(rec + p.G * D + qh, m);
-                shared_store(rec + p.G * D + p.G + qh, lt);
+                shared_store1(rec + (p.G * D + qh) * 4u, m);
+                shared_store1(rec + (p.G * D + p.G + qh) * 4u, lt);
             }
         }
     }
 
-    static __device__ inline void shared_store(float* ptr, float v)
+    // Records are shared between compute units that sit behind different L2 caches.  They are
+    // written and read with device-coherent accesses (sc1: write-through stores, loads that
+    // bypass the non-coherent cache levels), so that no cache-wide write-back or invalidate is
+    // ever needed.  `off` is a byte offset into the record area; the buffer descriptor bounds
+    // every access to that area.
+    static constexpr int kDeviceCoherent = 16;  // cache-policy bit sc1
+    __device__ inline void shared_store4(unsigned off, f32x4 v) const
     {
-        __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), records, off, 0, kDeviceCoherent);
     }
-    static __device__ inline float shared_load(const float* ptr)
+    __device__ inline void shared_store1(unsigned off, float v) const
     {
-        return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), records, off, 0, kDeviceCoherent);
+    }
+    __device__ inline f32x4 shared_load4(unsigned off) const
+    {
+        return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(records, off, 0, kDeviceCoherent));
+    }
+    __device__ inline float shared_load1(unsigned off) const
+    {
+        return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(records, off, 0, kDeviceCoherent));
     }
 
     // ---- epilogue: arrival counters and last-arriver merge -------------------------------------
@@ -428,10 +449,10 @@ struct Wave {
     __device__ inline void merge(int bkv, int a, int w0, int w1)
     {
         constexpr int K = 2 * QKB;   // float4 groups per lane: G*D*2 <= QKB KiB, so G*D/4 <= 128*QKB groups
-        constexpr int PB = 16 / K;   // pieces per batch
+        constexpr int PB = 32 / K;   // pieces per batch
         const int G = p.G;
         const int groups = G * D / 4;
-        const int rec_floats = record_floats(G, D);
+        const unsigned rec_bytes = record_floats(G, D) * 4u;
         int idx[K], qrow[K];
 #pragma unroll
         for (int k = 0; k < K; ++k) {
@@ -451,14 +472,13 @@ struct Wave {
             for (int i = 0; i < PB; ++i) {
                 const int wi = min(w + i, w1);  // the tail of a batch re-reads the last piece and is ignored below
                 const int slot = (a < wi * span) ? 0 : 1;
-                const float* rec = p.partials + static_cast<size_t>(wi * 2 + slot) * rec_floats;
+                const unsigned rec = static_cast<unsigned>(wi * 2 + slot) * rec_bytes;
 #pragma unroll
                 for (int k = 0; k < K; ++k) {
                     if (idx[k] < 0) continue;
-                    mm[i][k] = shared_load(rec + G * D + qrow[k]);
-                    ll[i][k] = shared_load(rec + G * D + G + qrow[k]);
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) aa[i][k][r] = shared_load(rec + idx[k] * 4 + r);
+                    mm[i][k] = shared_load1(rec + (G * D + qrow[k]) * 4u);
+                    ll[i][k] = shared_load1(rec + (G * D + G + qrow[k]) * 4u);
+                    aa[i][k] = shared_load4(rec + idx[k] * 16u);
                 }
             }
 #pragma unroll
@@ -494,15 +514,23 @@ struct Wave {
         }
     }
 
+    __amdgpu_buffer_rsrc_t records;  // the record area of the workspace
     int wave;       // index of this wave on the work line
     int span;       // page-units per wave
     int first_bkv, first_n, first_pg0;  // the stream the span begins in, and the page it begins at
 
     template <int S>
-    __device__ inline void prologue_stage(int total)
+    __device__ inline void plan_stage(int total, Planned* rs)
     {
-        if (S < total) produce<S>();
-        if constexpr (S + 1 < NS) prologue_stage<S + 1>(total);
+        if (S < total) plan(rs[S]);
+        if constexpr (S + 1 < NS) plan_stage<S + 1>(total, rs);
+    }
+
+    template <int S>
+    __device__ inline void issue_stage(int total, const Planned* rs)
+    {
+        if (S < total) issue<S>(rs[S]);
+        if constexpr (S + 1 < NS) issue_stage<S + 1>(total, rs);
     }
 
     template <int S>
@@ -511,9 +539,11 @@ struct Wave {
         const int i = base + S;
         if (i < total) {
             wait_stage<Geo::kLoadsPerStage, NS>(min(NS - 1, total - 1 - i));
-            if (i == 0) JD_STAMP(wave, 4);
             consume<S>();
-            if (i + NS < total) produce<S>();
+            if (i + NS < total) {
+                issue<S>(nx);                       // its block-table entry was requested a page ago
+                if (i + NS + 1 < total) plan(nx);
+            }
         }
         if constexpr (S + 1 < NS) round_stage<S + 1>(base, total);
     }
@@ -521,7 +551,10 @@ struct Wave {
     __device__ inline void run()
     {
         const int total = u1 - u0;
-        prologue_stage<0>(total);
+        Planned rs[NS];
+        plan_stage<0>(total, rs);   // the block-table entries of the first stages are all requested at once
+        issue_stage<0>(total, rs);
+        if (NS < total) plan(nx);
         JD_STAMP(wave, 3);
         for (int base = 0; base < total; base += NS) round_stage<0>(base, total);
         JD_STAMP(wave, 5);
@@ -595,8 +628,7 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
     scan_pages(p, s_cum, s_part);
     JD_STAMP(blockIdx.x * kWaves + (threadIdx.x >> 6), 1);
     const int units = s_cum[p.B] * p.Hkv;
-    int span = (units + p.slots - 1) / p.slots;
-    if (span < kMinSpan) span = kMinSpan;
+    const int span = span_for(units, p.slots);
     const int active = (units + span - 1) / span;
 
     const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -655,6 +687,7 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
     w.lds_ptr = (lds_char*)ring + wave_in_block * W::Geo::kWaveBytes;
     w.lds_wave = static_cast<unsigned>(reinterpret_cast<uintptr_t>(w.lds_ptr));
     w.init_lane_tables();
+    w.records = __builtin_amdgcn_make_buffer_rsrc(p.partials, 0, static_cast<int>(2u * p.slots * record_floats(p.G, D) * 4u), 0x00020000);
     w.cur.upos = w.u0;
     w.cur.b = sb;
     w.cur.kv = skv;
@@ -670,7 +703,6 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
     w.first_bkv = w.cur.last_bkv;
     w.first_n = w.cur.n;
     w.first_pg0 = spg;
-    w.fetch_next_id();
     w.m = 0.f;
     w.l = 0.f;
     w.run();

@@ -41,6 +41,13 @@ struct Params {
     float scale_log2e;          // softmax_scale * log2(e): scores are kept in the exp2 domain
 };
 
+// Page-units per wave for a work line of `units`, and the number of waves that get any.
+inline __host__ __device__ int span_for(int units, int slots)
+{
+    int span = (units + slots - 1) / slots;
+    return span < kMinSpan ? kMinSpan : span;
+}
+
 inline __host__ __device__ int record_floats(int G, int D) { return G * (D + 2); }
 
 // Launchers (each enqueues on `stream` and returns hipGetLastError()).

@@ -66,8 +66,7 @@ __global__ __launch_bounds__(kThreads) void partition_kernel(Params p)
     }
     const int total_pages = carry.x;
     const int units = total_pages * p.Hkv;
-    int span = (units + p.slots - 1) / p.slots;
-    if (span < kMinSpan) span = kMinSpan;
+    const int span = span_for(units, p.slots);
     const int active = (units + span - 1) / span;
     if (tid == 0) {
         p.cum_pages[p.B] = total_pages;

@@ -1,0 +1,118 @@
+"""Host-only checks: the library loads and exports the whole C ABI, configuration errors are reported
+without a GPU, and the chunk schedule matches its plain-Python statement."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import partition_ref
+from paper_2604_23838_amd import binding as jb
+from paper_2604_23838_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "jigsaw_decode.h")).read()
+    declared = set(re.findall(r"\b(jd_[a-z_]+)\s*\(", header))
+    assert declared, "no declarations found"
+    assert declared == set(jb.EXPORTS)
+    lib = jb.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def good_config():
+    return jb.jd_config(4, 8, 2, 64, 16, 63, 100, 0.0, 0, 0)
+
+
+def test_config_validation_without_gpu():
+    assert jb.jd_validate_config(good_config()) == jb.JD_OK
+    assert jb.jd_workspace_bytes(good_config()) > 0
+    bad = [("head_dim", 96, jb.JD_ERR_UNSUPPORTED), ("page_size", 32, jb.JD_ERR_UNSUPPORTED),
+           ("num_kv_heads", 3, jb.JD_ERR_INVALID_ARG), ("batch", 0, jb.JD_ERR_INVALID_ARG),
+           ("num_pages", -1, jb.JD_ERR_INVALID_ARG), ("max_pages_per_seq", 0, jb.JD_ERR_INVALID_ARG),
+           ("variant", 9, jb.JD_ERR_UNSUPPORTED), ("cu_budget", -2, jb.JD_ERR_INVALID_ARG),
+           ("softmax_scale", float("nan"), jb.JD_ERR_INVALID_ARG), ("softmax_scale", -1.0, jb.JD_ERR_INVALID_ARG)]
+    for field, value, want in bad:
+        c = good_config()
+        setattr(c, field, value)
+        assert jb.jd_validate_config(c) == want, field
+        assert jb.jd_last_error_string() != "no error"
+        assert jb.jd_workspace_bytes(c) == 0
+        with pytest.raises(jb.JdError) as e:   # rejected before any GPU call
+            jb.jd_create(c)
+        assert e.value.status == want
+    c = good_config()
+    c.num_q_heads, c.num_kv_heads = 34, 2      # group of 17 rows does not fit a 16-row tile
+    assert jb.jd_validate_config(c) == jb.JD_ERR_UNSUPPORTED
+    c = good_config()
+    c.num_q_heads, c.num_kv_heads, c.variant = 6, 2, jb.JD_VARIANT_VECTOR   # group size 3: matrix-core variant only
+    assert jb.jd_validate_config(c) == jb.JD_ERR_UNSUPPORTED
+    c.variant = jb.JD_VARIANT_MFMA
+    assert jb.jd_validate_config(c) == jb.JD_OK
+    c = good_config()
+    c.batch, c.max_pages_per_seq, c.num_kv_heads, c.num_q_heads = 1 << 20, 1 << 10, 8, 8
+    assert jb.jd_validate_config(c) == jb.JD_ERR_INVALID_ARG
+
+
+def test_null_handle_and_pointer_errors_without_gpu():
+    lib = jb.lib()
+    assert lib.jd_decode_attention(None, 1, 1, 1, 1, 1, 1, None) == jb.JD_ERR_INVALID_ARG
+    assert lib.jd_check_device_flags(None, None) == jb.JD_ERR_INVALID_ARG
+    assert lib.jd_debug_partition(None, None, None, None, None, None) == jb.JD_ERR_INVALID_ARG
+    assert lib.jd_profile_enable(None, 1, 1) == jb.JD_ERR_INVALID_ARG
+    assert lib.jd_destroy(None) == jb.JD_OK
+    assert lib.jd_wave_slots(None) == 0
+    assert lib.jd_debug_stream_read(None, 16, None, None) == jb.JD_ERR_INVALID_ARG
+    assert lib.jd_debug_stream_copy(None, None, 16, None) == jb.JD_ERR_INVALID_ARG
+
+
+def test_schedule_matches_reference():
+    rng = np.random.default_rng(0)
+    cases = [(0, 1024), (1, 1024), (4095, 1024), (4096, 1024), (4097, 1024), (478_616, 1024), (87_736, 1024),
+             (2_000_000_000, 4096), (500, 4)]
+    cases += [(int(u), int(s)) for u, s in zip(rng.integers(0, 5_000_000, 200), rng.choice([4, 28, 1024, 2048], 200))]
+    for units, slots in cases:
+        span, active = partition_ref.schedule(units, slots)
+        assert jb.jd_debug_schedule(units, slots) == [span, active], (units, slots)
+        assert active <= slots and (active - 1) * span < units <= active * span or units == 0
+
+
+def test_reference_partition_covers_every_page_once():
+    rng = np.random.default_rng(1)
+    lens = np.floor(rng.lognormal(np.log(700.0), 1.2, size=300)).astype(int).clip(0, 9000)
+    lens[::17] = 0
+    hkv, slots, maxp = 2, 64, 2048
+    hdr, starts, cum = partition_ref.partition(lens, hkv, slots, maxp)
+    segs = partition_ref.segments(lens, hkv, slots, maxp)
+    seen = {}
+    for w, b, kv, p0, p1 in segs:
+        assert p1 > p0
+        for pg in range(p0, p1):
+            assert (b, kv, pg) not in seen
+            seen[(b, kv, pg)] = w
+    assert len(seen) == hdr[0] == sum(partition_ref.pages(int(L), maxp) for L in lens) * hkv
+    # every wave gets the same number of units (the last one the remainder), in line order
+    per_wave = np.bincount([w for w, *_ in segs for _ in range(1)], minlength=hdr[2])
+    units = np.zeros(hdr[2], dtype=int)
+    for w, b, kv, p0, p1 in segs:
+        units[w] += p1 - p0
+    assert (units[:-1] == hdr[1]).all() and 0 < units[-1] <= hdr[1] and per_wave.min() >= 1
+    # the first segment of every wave is where wave_start says it begins
+    first = {}
+    for w, b, kv, p0, _ in segs:
+        first.setdefault(w, [b, kv, p0, 0])
+    assert [first[w] for w in range(hdr[2])] == starts
+
+
+def test_generator_matches_documented_totals():
+    # totals of the benchmark recipe (seed 0): a change of the generator would silently move the benchmark
+    want = {2: 957_219, 3: 175_455, 4: 810_848, 5: 1_738_022}
+    for cfg, total in want.items():
+        lens = W.draw_seq_lens(cfg, np.random.default_rng(0))
+        assert int(lens.sum()) == total
+    w = W.gen_config(1, 0)
+    assert w.total_tokens == 1367 and w.kv_bytes == 1367 * 2 * 2 * 64 * 2
+    assert w.block_table.min() == -1 and len(set(w.block_table[w.block_table >= 0].tolist())) == (w.block_table >= 0).sum()
