@@ -147,7 +147,7 @@ struct Wave {
     unsigned k_rd[D / 32], v_rd[D / 16], q_rd[D / 32];
     int meta[NS], dest[NS];
     Cursor cur;
-    Planned nx;
+    Planned nx, rs[NS];
     // consumer state (lane = query row q = lane % 16; token group tg = lane / 16)
     bf16x8 qreg[D / 32];
     f32x4 acc[D / 16];
@@ -548,11 +548,16 @@ struct Wave {
         if constexpr (S + 1 < NS) round_stage<S + 1>(base, total);
     }
 
+    // Request the block-table entries of the first stages, all at once.  Touches no LDS, so it can run
+    // while the block is still busy with the partition tables.
+    __device__ inline void begin()
+    {
+        plan_stage<0>(u1 - u0, rs);
+    }
+
     __device__ inline void run()
     {
         const int total = u1 - u0;
-        Planned rs[NS];
-        plan_stage<0>(total, rs);   // the block-table entries of the first stages are all requested at once
         issue_stage<0>(total, rs);
         if (NS < total) plan(nx);
         JD_STAMP(wave, 3);
@@ -651,6 +656,33 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
     skv = __builtin_amdgcn_readfirstlane(skv);
     spg = __builtin_amdgcn_readfirstlane(spg);
 
+    // the wave's cursor, and the block-table entries of its first pages (their latency overlaps the
+    // rest of the prologue)
+    W w(p);
+    w.lane = threadIdx.x & 63;
+    w.wave = wave;
+    w.span = span;
+    w.u0 = wave * span;
+    w.u1 = min(w.u0 + span, units);
+    if (wave < active && !partition_only) {
+        w.cur.upos = w.u0;
+        w.cur.b = sb;
+        w.cur.kv = skv;
+        w.cur.pg = spg;
+        const int L = uniform_load(p.seq_lens + sb);
+        w.cur.n = pages_of(p, L);
+        w.cur.L = L > w.cur.n * kPage ? w.cur.n * kPage : L;
+        w.cur.seg_pg0 = spg;
+        w.cur.seg_at_start = 1;
+        w.cur.last_bkv = sb * p.Hkv + skv;
+        w.cur.last_n = w.cur.n;
+        w.cur.last_a = w.u0 - spg;
+        w.first_bkv = w.cur.last_bkv;
+        w.first_n = w.cur.n;
+        w.first_pg0 = spg;
+        w.begin();
+    }
+
     // rows of requests without tokens
     for (int b = blockIdx.x; b < p.B && !partition_only; b += gridDim.x) {
         if (s_cum[b + 1] == s_cum[b]) {
@@ -672,39 +704,18 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
         i32x4 ws = {sb, skv, spg, sb};
         reinterpret_cast<i32x4*>(p.wave_start)[wave] = ws;
     }
+    w.lds_ptr = (lds_char*)ring + wave_in_block * W::Geo::kWaveBytes;
+    w.lds_wave = static_cast<unsigned>(reinterpret_cast<uintptr_t>(w.lds_ptr));
+    w.init_lane_tables();
+    w.records = __builtin_amdgcn_make_buffer_rsrc(p.partials, 0, static_cast<int>(2u * p.slots * record_floats(p.G, D) * 4u), 0x00020000);
+    w.m = 0.f;
+    w.l = 0.f;
     __syncthreads();  // the scratch is dead from here on
     if (partition_only || wave >= active) return;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     JD_STAMP(wave, 2);
 
     // ---- main loop and epilogue ----
-    W w(p);
-    w.lane = threadIdx.x & 63;
-    w.wave = wave;
-    w.span = span;
-    w.u0 = wave * span;
-    w.u1 = min(w.u0 + span, units);
-    w.lds_ptr = (lds_char*)ring + wave_in_block * W::Geo::kWaveBytes;
-    w.lds_wave = static_cast<unsigned>(reinterpret_cast<uintptr_t>(w.lds_ptr));
-    w.init_lane_tables();
-    w.records = __builtin_amdgcn_make_buffer_rsrc(p.partials, 0, static_cast<int>(2u * p.slots * record_floats(p.G, D) * 4u), 0x00020000);
-    w.cur.upos = w.u0;
-    w.cur.b = sb;
-    w.cur.kv = skv;
-    w.cur.pg = spg;
-    const int L = uniform_load(p.seq_lens + sb);
-    w.cur.n = pages_of(p, L);
-    w.cur.L = L > w.cur.n * kPage ? w.cur.n * kPage : L;
-    w.cur.seg_pg0 = spg;
-    w.cur.seg_at_start = 1;
-    w.cur.last_bkv = sb * p.Hkv + skv;
-    w.cur.last_n = w.cur.n;
-    w.cur.last_a = w.u0 - spg;
-    w.first_bkv = w.cur.last_bkv;
-    w.first_n = w.cur.n;
-    w.first_pg0 = spg;
-    w.m = 0.f;
-    w.l = 0.f;
     w.run();
 }
 
