@@ -7,7 +7,7 @@
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kBlocksPerCu = 8;
+constexpr int kBlocksPerCu = 2;  // measured best for the read sweep: all CUs move through one 8 MiB window
 
 __global__ __launch_bounds__(kThreads) void stream_read_kernel(const uint4* __restrict__ src, size_t n16, unsigned* sink)
 {

@@ -101,6 +101,19 @@ def test_ragged_batch_many_tiles(torch_cuda, jo, variant):
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
+def test_wide_batch_of_short_requests(torch_cuda, jo, variant):
+    # more requests than threads in a block (the partition scan takes several requests per thread), many of
+    # them empty or a single token
+    rng = np.random.default_rng(12)
+    lens = rng.integers(0, 70, size=3001).astype(np.int32)
+    lens[rng.integers(0, 3001, size=600)] = 0
+    lens[-1] = 777
+    w = W.build(W.SHAPES[5], lens, seed=12, cfg=94)
+    ref = jo.decode_attention(*arrays(w))
+    check(run_gpu(torch_cuda, arrays(w), variant), ref, f"wide batch v{variant}")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
 def test_scale_override_and_sharp_softmax(torch_cuda, jo, variant):
     # large scale: the softmax is dominated by a few tokens; exercises the running-max rescale
     w = W.gen_config(1, 3)
@@ -186,6 +199,83 @@ def test_bad_page_id_is_flagged_not_dereferenced(torch_cuda):
         with pytest.raises(jb.JdError) as e:
             run_gpu(torch_cuda, (w.q, w.k_pages, w.v_pages, bt, w.seq_lens), variant)
         assert e.value.status == jb.JD_ERR_BAD_INPUT
+
+
+def _to_dev(torch, arrs):
+    dev = torch.device("cuda:0")
+    q, kp, vp, bt, lens = arrs
+    return (torch.from_numpy(q.view(np.int16)).to(dev).view(torch.bfloat16),
+            torch.from_numpy(kp.view(np.int16)).to(dev).view(torch.bfloat16),
+            torch.from_numpy(vp.view(np.int16)).to(dev).view(torch.bfloat16),
+            torch.from_numpy(bt).to(dev), torch.from_numpy(lens).to(dev))
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_handle_reuse_with_changing_lengths(torch_cuda, jo, variant):
+    # one handle, one pool, three steps whose lengths (hence partition, split sequences and partial records)
+    # differ: records and arrival counters left by one call must not leak into the next
+    from paper_2604_23838_amd import binding as jb
+    torch = torch_cuda
+    shp = W.SHAPES[2]
+    w = W.build(shp, [9000, 40, 3000, 700, 16, 5000, 1, 260], seed=4, cfg=92)
+    tq, tk, tv, tbt, tl = _to_dev(torch, arrays(w))
+    op = jb.DecodeAttention(8, shp.num_q_heads, shp.num_kv_heads, shp.head_dim, w.max_pages_per_seq, w.num_pages,
+                            variant=variant)
+    rng = np.random.default_rng(0)
+    for step in range(4):
+        lens = w.seq_lens.copy() if step == 0 else np.minimum(w.seq_lens, rng.integers(0, 9001, size=8)).astype(np.int32)
+        if step == 2:
+            lens[:] = [0, 0, 2999, 0, 0, 0, 1, 0]
+        tl.copy_(torch.from_numpy(lens))
+        out = torch.full((8, shp.num_q_heads, shp.head_dim), float("nan"), dtype=torch.float32, device="cuda:0")
+        op(tq, tk, tv, tbt, tl, out)
+        torch.cuda.synchronize()
+        ref = jo.decode_attention(w.q, w.k_pages, w.v_pages, w.block_table, lens)
+        check(out.cpu().numpy(), ref, f"reuse step {step} v{variant}")
+    op.check_flags()
+    op.close()
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_hip_graph_capture_and_replay(torch_cuda, jo, variant):
+    # the call only enqueues kernels, so it can be captured; every replay (with the program's own eager work and
+    # synchronisations in between, and with new lengths written into the captured buffers) must match the oracle
+    from paper_2604_23838_amd import binding as jb
+    torch = torch_cuda
+    shp = W.SHAPES[5]
+    w = W.build(shp, [300, 2500, 17, 64, 1200, 8000], seed=6, cfg=93)
+    tq, tk, tv, tbt, tl = _to_dev(torch, arrays(w))
+    B = 6
+    op = jb.DecodeAttention(B, shp.num_q_heads, shp.num_kv_heads, shp.head_dim, w.max_pages_per_seq, w.num_pages,
+                            variant=variant)
+    out = torch.zeros((B, shp.num_q_heads, shp.head_dim), dtype=torch.float32, device="cuda:0")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        op(tq, tk, tv, tbt, tl, out)      # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    eager = out.cpu().numpy().copy()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        op(tq, tk, tv, tbt, tl, out)
+    rng = np.random.default_rng(1)
+    lens = w.seq_lens.copy()
+    for rep in range(4):
+        if rep:
+            lens = np.minimum(w.seq_lens, rng.integers(1, 8001, size=B)).astype(np.int32)
+            tl.copy_(torch.from_numpy(lens))
+        out.fill_(float("nan"))          # eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        ref = jo.decode_attention(w.q, w.k_pages, w.v_pages, w.block_table, lens)
+        check(got, ref, f"graph replay {rep} v{variant}")
+        if rep == 0:
+            assert np.array_equal(got.view(np.uint32), eager.view(np.uint32))
+    op.check_flags()
+    op.close()
 
 
 FULL = {2: "qwen3-8b-like", 3: "stragglers", 4: "qwen3-32b-like", 5: "qwen2.5-0.5b-like"}
