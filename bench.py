@@ -34,6 +34,10 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--variant", type=int, default=0, help="0 default, 1 vector, 2 mfma")
     ap.add_argument("--cu-budget", type=int, default=0)
+    ap.add_argument("--sweep", choices=["none", "cu", "batch"], default="none",
+                    help="extra measurements after the timed region: 'cu' = step time at 25/50/75/100 %% of the "
+                         "compute units (the library's cu_budget), 'batch' = step time as the batch shrinks to its "
+                         "longest requests")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="CPU-seconds budget of the oracle sample")
     args = ap.parse_args()
@@ -147,6 +151,50 @@ def main() -> int:
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic},
     }
+
+    def time_steps(o, lens_t, steps=60, warm=10):
+        with torch.cuda.stream(stream):
+            for _ in range(warm):
+                o(q, kp, vp, bt, lens_t, out)
+            torch.cuda.synchronize()
+            t0_ = time.perf_counter()
+            for _ in range(steps):
+                o(q, kp, vp, bt, lens_t, out)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0_) * 1e6 / steps
+
+    if args.sweep == "cu":
+        # the paper bounds the SMs a sub-stage may use and finds small-batch rollout insensitive to them
+        # (Sub-stage Multiplexing, "Compute Resource Utilization"); the same experiment with the library's CU budget
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        rows = []
+        for pct in (25, 50, 75, 100):
+            o2 = jb.DecodeAttention(s.batch, s.num_q_heads, s.num_kv_heads, s.head_dim, w.max_pages_per_seq,
+                                    w.num_pages, variant=args.variant, cu_budget=cus * pct // 100)
+            us = time_steps(o2, sl)
+            o2.close()
+            rows.append({"cu_pct": pct, "cu_budget": cus * pct // 100, "us_per_step": round(us, 2),
+                         "kv_tb_per_s": round(kv_bytes / us / 1e6, 4)})
+        result["cu_budget_sweep"] = rows
+    if args.sweep == "batch":
+        # the effective batch shrinks as short responses finish (Motivation, "Varied Decoding Lengths"):
+        # keep the k longest requests active, the others are finished rows (seq_len 0) of the same batch
+        order = np.argsort(-w.seq_lens.astype(np.int64), kind="stable")
+        rows = []
+        k = s.batch
+        while k >= 1:
+            lens_k = np.zeros_like(w.seq_lens)
+            lens_k[order[:k]] = w.seq_lens[order[:k]]
+            lt = torch.from_numpy(lens_k).to(dev)
+            us = time_steps(op, lt)
+            kvb = int(lens_k.astype(np.int64).sum()) * 2 * s.num_kv_heads * s.head_dim * 2
+            rows.append({"active_requests": k, "tokens": int(lens_k.astype(np.int64).sum()), "us_per_step": round(us, 2),
+                         "kv_tb_per_s": round(kvb / us / 1e6, 4)})
+            k //= 2
+        result["shrinking_batch_sweep"] = rows
+        with torch.cuda.stream(stream):
+            op(q, kp, vp, bt, sl, out)     # restore the full batch's output for the parity check below
+            torch.cuda.synchronize()
 
     if not args.no_cpu_baseline:
         from oracle import jo

@@ -19,13 +19,13 @@ def pages(L: int, max_pages: int) -> int:
     return min(n, max_pages)
 
 
-def schedule(units: int, slots: int, min_span: int = 4):
+def schedule(units: int, slots: int, min_span: int = 16):
     """(span, active_waves) for a work line of `units` page-units."""
     span = max(min_span, -(-units // slots))
     return span, -(-units // span)
 
 
-def partition(seq_lens, num_kv_heads: int, slots: int, max_pages: int, min_span: int = 4):
+def partition(seq_lens, num_kv_heads: int, slots: int, max_pages: int, min_span: int = 16):
     """Returns (header, wave_start, cum_pages) as the library reports them:
     header = [units, span, active_waves, slots];
     wave_start[w] = [request, kv head, page, 0] for w < active_waves."""
@@ -46,7 +46,7 @@ def partition(seq_lens, num_kv_heads: int, slots: int, max_pages: int, min_span:
     return [units, span, active, slots], starts, cum
 
 
-def segments(seq_lens, num_kv_heads: int, slots: int, max_pages: int, min_span: int = 4):
+def segments(seq_lens, num_kv_heads: int, slots: int, max_pages: int, min_span: int = 16):
     """Every (wave, request, kv head, first page, end page) piece of the partition, by walking the line."""
     n = [pages(int(L), max_pages) for L in seq_lens]
     units = sum(n) * num_kv_heads

@@ -7,7 +7,7 @@
 namespace jd {
 
 constexpr int kPage = 16;          // tokens per KV page
-constexpr int kMinSpan = 4;        // smallest share of work (page-units) a wave is given
+constexpr int kMinSpan = 16;       // smallest share of work (page-units) a wave is given
 constexpr int kMaxWaveSlots = 4096;
 constexpr int kHeaderInts = 64;
 
