@@ -27,22 +27,27 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def load_library(path: str):
+    """Load an oracle shared library and declare its signatures."""
+    lib = C.CDLL(path)
+    p = C.c_void_p
+    common = [p, p, p, p, p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double]
+    lib.jo_decode_attention.argtypes = common + [p, C.c_int, p, p, C.c_int]
+    lib.jo_decode_attention.restype = C.c_int
+    lib.jo_softmax_weights.argtypes = common + [C.c_int, C.c_int, p]
+    lib.jo_softmax_weights.restype = C.c_int
+    lib.jo_partial_state.argtypes = common + [C.c_int, C.c_int, p, C.c_int, p, p, p]
+    lib.jo_partial_state.restype = C.c_int
+    lib.jo_merge_states.argtypes = [C.c_int, p, p, p, C.c_int, p]
+    lib.jo_merge_states.restype = C.c_int
+    lib.jo_max_threads.restype = C.c_int
+    return lib
+
+
 def _load():
     global _lib
     if _lib is None:
-        lib = C.CDLL(build())
-        p = C.c_void_p
-        common = [p, p, p, p, p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double]
-        lib.jo_decode_attention.argtypes = common + [p, C.c_int, p, p, C.c_int]
-        lib.jo_decode_attention.restype = C.c_int
-        lib.jo_softmax_weights.argtypes = common + [C.c_int, C.c_int, p]
-        lib.jo_softmax_weights.restype = C.c_int
-        lib.jo_partial_state.argtypes = common + [C.c_int, C.c_int, p, C.c_int, p, p, p]
-        lib.jo_partial_state.restype = C.c_int
-        lib.jo_merge_states.argtypes = [C.c_int, p, p, p, C.c_int, p]
-        lib.jo_merge_states.restype = C.c_int
-        lib.jo_max_threads.restype = C.c_int
-        _lib = lib
+        _lib = load_library(build())
     return _lib
 
 

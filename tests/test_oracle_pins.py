@@ -251,3 +251,23 @@ def test_empty_request_gives_zero_row_and_rows_subset(jo):
         assert np.array_equal(sub[i], out[b, h])
     one = jo.decode_attention(*args, threads=1)
     assert np.array_equal(one, out)
+
+
+def test_frozen_outputs_of_tiny_config(jo):
+    # regression guard: values written by tests/golden/make_expected.py (oracle only)
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "cfg1_seed0_expected.txt")
+    w = W.gen_config(1, 0)
+    out = jo.decode_attention(w.q, w.k_pages, w.v_pages, w.block_table, w.seq_lens)
+    n = 0
+    for line in open(path):
+        if line.startswith("#"):
+            continue
+        parts = line.split()
+        b, h = int(parts[0]), int(parts[1])
+        bits = np.array([int(x, 16) for x in parts[2:12]], dtype=np.uint32)
+        got = np.concatenate([out[b, h, :8], out[b, h, -2:]]).view(np.uint32)
+        assert np.array_equal(got, bits), (b, h)
+        assert abs(float(out[b, h].astype(np.float64).sum()) - float(parts[12])) < 1e-12
+        n += 1
+    assert n == 32
