@@ -111,6 +111,25 @@ jd_status jd_decode_attention(jd_handle *h, const void *q, const void *k_pages, 
                               void *stream);
 
 /*
+ * The write half of a decode step: append one token per active request to the paged cache and
+ * bump its length, so that the jd_decode_attention call that follows attends over it (a decode
+ * forward step processes the active decoding requests and grows their KV cache by one token:
+ * System Design, "Sub-Stage Graph Abstraction"; Sub-stage Multiplexing, "GPU Memory Utilization").
+ *   k_new, v_new  bf16 [B, Hkv, D]        device, 16-byte aligned, read: the new token's rows
+ *   k_pages, v_pages  bf16 [NP, Hkv, 16, D]   device, 16-byte aligned, written in place
+ *   block_table   int32 [B, MAXP]          device, read; the page of slot L must already be assigned
+ *   seq_lens      int32 [B]                device, read and written: L -> L + 1 for active requests
+ *   active        int32 [B] or NULL        device, read; non-zero = append.  NULL: every request
+ *                                          with L > 0 appends (rows with L = 0 are finished slots)
+ * For an active request with L tokens the rows go to slot L % 16 of page block_table[b][L / 16].
+ * A request whose next slot lies beyond 16*MAXP, or whose page id is outside [0, NP), is left
+ * unchanged and raises the sticky flag reported by jd_check_device_flags.  Only enqueues on
+ * `stream`; may be captured into a HIP graph together with jd_decode_attention.
+ */
+jd_status jd_append_kv(jd_handle *h, const void *k_new, const void *v_new, void *k_pages, void *v_pages,
+                       const int32_t *block_table, int32_t *seq_lens, const int32_t *active, void *stream);
+
+/*
  * Synchronise `stream` and report device-side input checks of the calls completed so far:
  * JD_OK, JD_ERR_BAD_INPUT (and clears the flag) or JD_ERR_HIP.
  */

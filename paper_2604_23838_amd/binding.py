@@ -16,7 +16,7 @@ LIB_PATH = os.environ.get("JIGSAW_DECODE_LIB") or os.path.join(_HERE, "libjigsaw
 JD_OK, JD_ERR_INVALID_ARG, JD_ERR_UNSUPPORTED, JD_ERR_HIP, JD_ERR_BAD_INPUT = range(5)
 JD_VARIANT_DEFAULT, JD_VARIANT_VECTOR, JD_VARIANT_MFMA = range(3)
 
-EXPORTS = ("jd_validate_config", "jd_workspace_bytes", "jd_create", "jd_decode_attention",
+EXPORTS = ("jd_validate_config", "jd_workspace_bytes", "jd_create", "jd_decode_attention", "jd_append_kv",
            "jd_check_device_flags", "jd_debug_partition", "jd_profile_enable", "jd_profile_read",
            "jd_debug_stream_read", "jd_debug_stream_copy",
            "jd_debug_schedule", "jd_wave_slots", "jd_destroy",
@@ -56,6 +56,8 @@ def lib():
         l.jd_create.restype = C.c_int
         l.jd_decode_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
         l.jd_decode_attention.restype = C.c_int
+        l.jd_append_kv.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        l.jd_append_kv.restype = C.c_int
         l.jd_check_device_flags.argtypes = [vp, vp]
         l.jd_check_device_flags.restype = C.c_int
         l.jd_debug_partition.argtypes = [vp, vp, vp, vp, vp, vp]
@@ -103,6 +105,13 @@ def jd_create(cfg: jd_config):
 def jd_decode_attention(handle, q, k_pages, v_pages, block_table, seq_lens, out, stream=0) -> None:
     """All tensor arguments are device addresses (ints); `stream` is a hipStream_t value."""
     st = lib().jd_decode_attention(handle, q, k_pages, v_pages, block_table, seq_lens, out, stream)
+    if st != JD_OK:
+        raise JdError(st, jd_last_error_string(handle))
+
+
+def jd_append_kv(handle, k_new, v_new, k_pages, v_pages, block_table, seq_lens, active=None, stream=0) -> None:
+    """Device addresses (ints); `active` may be None."""
+    st = lib().jd_append_kv(handle, k_new, v_new, k_pages, v_pages, block_table, seq_lens, active, stream)
     if st != JD_OK:
         raise JdError(st, jd_last_error_string(handle))
 
@@ -211,6 +220,21 @@ class DecodeAttention:
         jd_decode_attention(self.handle, q.data_ptr(), k_pages.data_ptr(), v_pages.data_ptr(),
                             block_table.data_ptr(), seq_lens.data_ptr(), out.data_ptr(), s.cuda_stream)
         return out
+
+    def append(self, k_new, v_new, k_pages, v_pages, block_table, seq_lens, active=None, stream=None):
+        """Append one token per active request (k_new, v_new: bf16 [B, Hkv, D]) and bump seq_lens in place."""
+        import torch
+        c = self.cfg
+        for t in (k_new, v_new):
+            if not (t.is_cuda and t.dtype == torch.bfloat16 and tuple(t.shape) == (c.batch, c.num_kv_heads, c.head_dim)
+                    and t.is_contiguous()):
+                raise ValueError("k_new / v_new must be contiguous CUDA bf16 [B, Hkv, D]")
+        if active is not None and not (active.is_cuda and active.dtype == torch.int32 and tuple(active.shape) == (c.batch,)):
+            raise ValueError("active must be a CUDA int32 [B] tensor")
+        s = torch.cuda.current_stream() if stream is None else stream
+        jd_append_kv(self.handle, k_new.data_ptr(), v_new.data_ptr(), k_pages.data_ptr(), v_pages.data_ptr(),
+                     block_table.data_ptr(), seq_lens.data_ptr(), None if active is None else active.data_ptr(),
+                     s.cuda_stream)
 
     def check_flags(self, stream=None):
         import torch

@@ -209,6 +209,23 @@ jd_status jd_decode_attention(jd_handle* h, const void* q, const void* k_pages, 
     return JD_OK;
 }
 
+jd_status jd_append_kv(jd_handle* h, const void* k_new, const void* v_new, void* k_pages, void* v_pages,
+                       const int32_t* block_table, int32_t* seq_lens, const int32_t* active, void* stream)
+{
+    if (!h) return fail(nullptr, JD_ERR_INVALID_ARG, "handle is NULL");
+    if (!k_new || !v_new || !k_pages || !v_pages || !block_table || !seq_lens)
+        return fail(h, JD_ERR_INVALID_ARG, "k_new, v_new, k_pages, v_pages, block_table and seq_lens must be non-NULL");
+    if (misaligned(k_new) || misaligned(v_new) || misaligned(k_pages) || misaligned(v_pages))
+        return fail(h, JD_ERR_INVALID_ARG, "k_new, v_new, k_pages and v_pages must be 16-byte aligned");
+    jd::Params p = h->params;
+    p.block_table = block_table;
+    hipError_t e = jd::launch_append_kv(p, static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
+                                        static_cast<uint16_t*>(k_pages), static_cast<uint16_t*>(v_pages), seq_lens,
+                                        active, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(h, JD_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
+    return JD_OK;
+}
+
 jd_status jd_check_device_flags(jd_handle* h, void* stream)
 {
     if (!h) return fail(nullptr, JD_ERR_INVALID_ARG, "handle is NULL");

@@ -176,7 +176,7 @@ def build(shape: Shape, seq_lens, seed: int = 0, *, cfg: int = 0, poison: bool =
                 last = int(block_table[b, (L - 1) // PAGE])
                 k_pages[last, :, r:, :] = BF16_NAN
                 v_pages[last, :, r:, :] = BF16_NAN
-    return Workload(cfg, seed, shape, q, k_pages, v_pages, block_table, seq_lens)
+    return Workload(cfg, seed, dataclasses.replace(shape, batch=B), q, k_pages, v_pages, block_table, seq_lens)
 
 
 def gen_config(cfg: int, seed: int = 0, *, threads: int = 8, poison: bool = True) -> Workload:
