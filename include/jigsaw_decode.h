@@ -137,12 +137,16 @@ jd_status jd_check_device_flags(jd_handle *h, void *stream);
 
 /*
  * Run only the work partitioner for seq_lens (device, int32 [B]) and copy its tables to the
- * host (synchronises `stream`).  For tests and tuning.
- *   header_host      int32 [8]: {units, span, active_waves, wave_slots, 0, 0, 0, 0}
- *                    units = sum over requests of ceil(L/16) * Hkv page-units of work;
- *                    span = page-units per wave; wave w < active_waves owns units [w*span, min((w+1)*span, units))
- *   wave_start_host  int32 [wave_slots * 4]: {request, kv_head, page, 0} of the first unit of each active wave
- *                    (zeros for the inactive ones)
+ * host (synchronises `stream`).  For tests and tuning.  Waves work in groups of `group_waves`
+ * (1 for the vector variant): member i of a group serves the kv heads i, i + group_waves, ...; the
+ * work of a step is the line of group-units (request, kv-head group, page), request-major, then
+ * kv-head group, then page, and a group of waves owns one span of it.
+ *   header_host      int32 [8]: {units, span, active_groups, wave_slots, group_waves, 0, 0, 0}
+ *                    units = sum over requests of ceil(L/16) * Hkv / group_waves;
+ *                    group g < active_groups owns units [g*span, min((g+1)*span, units)) and consists of
+ *                    waves g*group_waves .. (g+1)*group_waves - 1
+ *   wave_start_host  int32 [wave_slots * 4]: {request, kv_head, page, 0} of the first page each wave of an
+ *                    active group works on (zeros for the others)
  *   cum_pages_host   int32 [B + 1]: pages of all requests before b (exclusive prefix of ceil(L/16))
  * Any of the three host pointers may be NULL.
  */

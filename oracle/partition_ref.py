@@ -25,40 +25,45 @@ def schedule(units: int, slots: int, min_span: int = 16):
     return span, -(-units // span)
 
 
-def partition(seq_lens, num_kv_heads: int, slots: int, max_pages: int, min_span: int = 16):
+def partition(seq_lens, num_kv_heads: int, slots: int, max_pages: int, group_waves: int = 1, min_span: int = 16):
     """Returns (header, wave_start, cum_pages) as the library reports them:
-    header = [units, span, active_waves, slots];
-    wave_start[w] = [request, kv head, page, 0] for w < active_waves."""
+    header = [units, span, active_groups, slots, group_waves];
+    wave_start[w] = [request, kv head, page, 0] for the waves of the active groups.
+    Waves work in groups of `group_waves`; member i of a group serves kv heads i, i + group_waves, ...;
+    the line is made of group-units (request, kv-head group, page) and a group owns one span of it."""
     n = [pages(int(L), max_pages) for L in seq_lens]
     cum = [0]
     for x in n:
         cum.append(cum[-1] + x)
-    units = cum[-1] * num_kv_heads
-    span = max(min_span, -(-units // slots))
-    active = -(-units // span)
-    # enumerate the line explicitly and read off where each wave starts
+    hg = num_kv_heads // group_waves
+    units = cum[-1] * hg
+    span, active = schedule(units, slots // group_waves, min_span)
+    # enumerate the line explicitly and read off where each group starts
     starts = []
-    line = ((b, kv, pg) for b in range(len(n)) for kv in range(num_kv_heads) for pg in range(n[b]))
-    for u, (b, kv, pg) in enumerate(line):
+    line = ((b, kvg, pg) for b in range(len(n)) for kvg in range(hg) for pg in range(n[b]))
+    for u, (b, kvg, pg) in enumerate(line):
         if u % span == 0:
-            starts.append([b, kv, pg, 0])
-    assert len(starts) == active
-    return [units, span, active, slots], starts, cum
+            for i in range(group_waves):
+                starts.append([b, kvg * group_waves + i, pg, 0])
+    assert len(starts) == active * group_waves
+    return [units, span, active, slots, group_waves], starts, cum
 
 
-def segments(seq_lens, num_kv_heads: int, slots: int, max_pages: int, min_span: int = 16):
+def segments(seq_lens, num_kv_heads: int, slots: int, max_pages: int, group_waves: int = 1, min_span: int = 16):
     """Every (wave, request, kv head, first page, end page) piece of the partition, by walking the line."""
     n = [pages(int(L), max_pages) for L in seq_lens]
-    units = sum(n) * num_kv_heads
-    span = max(min_span, -(-units // slots))
+    hg = num_kv_heads // group_waves
+    units = sum(n) * hg
+    span, _ = schedule(units, slots // group_waves, min_span)
     out, u = [], 0
     for b in range(len(n)):
-        for kv in range(num_kv_heads):
+        for kvg in range(hg):
             pg = 0
             while pg < n[b]:
-                w = u // span
-                take = min(n[b] - pg, (w + 1) * span - u)
-                out.append((w, b, kv, pg, pg + take))
+                g = u // span
+                take = min(n[b] - pg, (g + 1) * span - u)
+                for i in range(group_waves):
+                    out.append((g * group_waves + i, b, kvg * group_waves + i, pg, pg + take))
                 pg += take
                 u += take
     return out

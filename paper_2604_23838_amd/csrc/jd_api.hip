@@ -172,6 +172,7 @@ jd_status jd_create(const jd_config* cfg, jd_handle** out)
     p.B = cfg->batch; p.Hq = cfg->num_q_heads; p.Hkv = cfg->num_kv_heads;
     p.G = p.Hq / p.Hkv; p.D = cfg->head_dim; p.maxp = cfg->max_pages_per_seq; p.NP = cfg->num_pages;
     p.slots = slots;
+    p.wg = h->variant == JD_VARIANT_VECTOR ? 1 : jd::mfma_group_waves(p.Hkv);
     const double scale = cfg->softmax_scale > 0.f ? static_cast<double>(cfg->softmax_scale) : 1.0 / std::sqrt(static_cast<double>(p.D));
     p.scale_log2e = static_cast<float>(scale * 1.4426950408889634);
     *out = h;
@@ -264,13 +265,15 @@ jd_status jd_debug_partition(jd_handle* h, const int32_t* seq_lens, int32_t* hea
     if (e != hipSuccess) return fail(h, JD_ERR_HIP, std::string("partition failed: ") + hipGetErrorString(e));
     if (header_host) {
         std::memcpy(header_host, hdr, sizeof hdr);
-        header_host[4] = header_host[5] = header_host[6] = header_host[7] = 0;
+        header_host[4] = hdr[jd::kHdrGroup];
+        header_host[5] = header_host[6] = header_host[7] = 0;
     }
     if (wave_start_host) {  // report {request, kv head, page, 0}
+        const int active_waves = hdr[jd::kHdrActive] * hdr[jd::kHdrGroup];
         for (int w = 0; w < p.slots; ++w) {
             int32_t* r = wave_start_host + 4 * w;
-            r[0] = w < hdr[jd::kHdrActive] ? r[3] : 0;
-            if (w >= hdr[jd::kHdrActive]) r[1] = r[2] = 0;
+            r[0] = w < active_waves ? r[3] : 0;
+            if (w >= active_waves) r[1] = r[2] = 0;
             r[3] = 0;
         }
     }

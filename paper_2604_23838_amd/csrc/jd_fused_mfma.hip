@@ -255,8 +255,9 @@ struct Wave {
         ++cur.upos;
         if (++cur.pg == cur.n) {
             cur.pg = 0;
-            if (++cur.kv == p.Hkv) {
-                cur.kv = 0;
+            cur.kv += p.wg;                 // the next kv head of this wave's lane in the group
+            if (cur.kv >= p.Hkv) {
+                cur.kv = member;
                 if (cur.upos < u1) next_request();
             }
         }
@@ -453,6 +454,7 @@ struct Wave {
         const int G = p.G;
         const int groups = G * D / 4;
         const unsigned rec_bytes = record_floats(G, D) * 4u;
+        const int rec_member = (bkv % p.Hkv) % p.wg;  // the piece of group g sits in the records of wave g*wg + member
         int idx[K], qrow[K];
 #pragma unroll
         for (int k = 0; k < K; ++k) {
@@ -472,7 +474,7 @@ struct Wave {
             for (int i = 0; i < PB; ++i) {
                 const int wi = min(w + i, w1);  // the tail of a batch re-reads the last piece and is ignored below
                 const int slot = (a < wi * span) ? 0 : 1;
-                const unsigned rec = static_cast<unsigned>(wi * 2 + slot) * rec_bytes;
+                const unsigned rec = static_cast<unsigned>((wi * p.wg + rec_member) * 2 + slot) * rec_bytes;
 #pragma unroll
                 for (int k = 0; k < K; ++k) {
                     if (idx[k] < 0) continue;
@@ -515,8 +517,9 @@ struct Wave {
     }
 
     __amdgpu_buffer_rsrc_t records;  // the record area of the workspace
-    int wave;       // index of this wave on the work line
-    int span;       // page-units per wave
+    int wave;       // index of this wave
+    int member;     // its place in its group of wg waves: it serves the kv heads congruent to member mod wg
+    int span;       // group-units per group of waves
     int first_bkv, first_n, first_pg0;  // the stream the span begins in, and the page it begins at
 
     template <int S>
@@ -632,24 +635,30 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
     int* s_part = s_cum + ((p.B + 1 + 63) & ~63);
     scan_pages(p, s_cum, s_part);
     JD_STAMP(blockIdx.x * kWaves + (threadIdx.x >> 6), 1);
-    const int units = s_cum[p.B] * p.Hkv;
-    const int span = span_for(units, p.slots);
-    const int active = (units + span - 1) / span;
+    // Waves work in groups of wg: the waves of a group walk the same (request, page) sequence, each on its
+    // own kv heads (member, member + wg, ...), so that together they read neighbouring kv heads of the
+    // same physical page at about the same time.  The work line is counted in group-units
+    // (request, kv-head group, page); a group of waves owns a span of it.
+    const int hg = p.Hkv / p.wg;
+    const int units = s_cum[p.B] * hg;
+    const int span = span_for(units, p.slots / p.wg);
+    const int active = (units + span - 1) / span;   // groups that own at least one unit
 
     const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * kWaves + wave_in_block);
+    const int group = wave / p.wg, member = wave % p.wg;
     int sb = 0, skv = 0, spg = 0;
-    if (wave < active) {
-        const int u = wave * span;
+    if (group < active) {
+        const int u = group * span;
         int lo = 0, hi = p.B - 1;  // the last request whose first unit is <= u
         while (lo < hi) {
             const int mid = (lo + hi + 1) >> 1;
-            if (s_cum[mid] * p.Hkv <= u) lo = mid; else hi = mid - 1;
+            if (s_cum[mid] * hg <= u) lo = mid; else hi = mid - 1;
         }
         const int n = s_cum[lo + 1] - s_cum[lo];
-        const int within = u - s_cum[lo] * p.Hkv;
+        const int within = u - s_cum[lo] * hg;
         sb = lo;
-        skv = within / n;
+        skv = (within / n) * p.wg + member;
         spg = within % n;
     }
     sb = __builtin_amdgcn_readfirstlane(sb);
@@ -661,10 +670,11 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
     W w(p);
     w.lane = threadIdx.x & 63;
     w.wave = wave;
+    w.member = member;
     w.span = span;
-    w.u0 = wave * span;
+    w.u0 = group * span;
     w.u1 = min(w.u0 + span, units);
-    if (wave < active && !partition_only) {
+    if (group < active && !partition_only) {
         w.cur.upos = w.u0;
         w.cur.b = sb;
         w.cur.kv = skv;
@@ -698,9 +708,10 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
             p.header[kHdrSpan] = span;
             p.header[kHdrActive] = active;
             p.header[kHdrSlots] = p.slots;
+            p.header[kHdrGroup] = p.wg;
         }
     }
-    if (wave < active && (threadIdx.x & 63) == 0) {
+    if (group < active && (threadIdx.x & 63) == 0) {
         i32x4 ws = {sb, skv, spg, sb};
         reinterpret_cast<i32x4*>(p.wave_start)[wave] = ws;
     }
@@ -711,7 +722,7 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
     w.m = 0.f;
     w.l = 0.f;
     __syncthreads();  // the scratch is dead from here on
-    if (partition_only || wave >= active) return;
+    if (partition_only || group >= active) return;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     JD_STAMP(wave, 2);
 
@@ -746,6 +757,14 @@ extern "C" int jd_debug_read_stamps(long long* host)
     return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_stamps), sizeof(long long) * kMaxWaveSlots * 8) == hipSuccess ? 0 : 1;
 }
 #endif
+
+// Waves per group: the largest power of two that divides the kv-head count and fits a block.
+int mfma_group_waves(int num_kv_heads)
+{
+    int wg = 1;
+    while (wg * 2 <= kWaves && num_kv_heads % (wg * 2) == 0) wg *= 2;
+    return wg;
+}
 
 int mfma_max_batch()
 {

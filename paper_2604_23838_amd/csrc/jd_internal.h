@@ -19,6 +19,7 @@ enum HeaderWord {
     kHdrSlots = 3,      // wave slots the partial pass is launched with
     kHdrNonEmpty = 4,   // requests with at least one token
     kHdrBadInput = 5,   // sticky flag: page id or length out of bounds seen
+    kHdrGroup = 6,      // waves per group (fused kernel; 1 = every wave on its own)
 };
 
 // Device pointers and sizes every kernel receives by value.
@@ -38,6 +39,7 @@ struct Params {
     float* partials;            // [slots * 2] records of G*(D+2) floats: acc[G][D], m[G], l[G]
     int32_t* counters;          // [B * Hkv] arrival counters of the fused kernel (zero between calls)
     int32_t B, Hq, Hkv, G, D, maxp, NP, slots;
+    int32_t wg;                 // waves per group in the fused kernel (divides Hkv and slots)
     float scale_log2e;          // softmax_scale * log2(e): scores are kept in the exp2 domain
 };
 
@@ -55,6 +57,7 @@ hipError_t launch_partition(const Params& p, hipStream_t stream);
 hipError_t launch_partial_vector(const Params& p, hipStream_t stream);
 hipError_t launch_fused_mfma(const Params& p, hipStream_t stream, int partition_only);
 int mfma_max_batch();
+int mfma_group_waves(int num_kv_heads);
 hipError_t launch_combine(const Params& p, hipStream_t stream);
 hipError_t launch_append_kv(const Params& p, const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pages,
                             uint16_t* v_pages, int32_t* seq_lens, const int32_t* active, hipStream_t stream);

@@ -75,6 +75,7 @@ __global__ __launch_bounds__(kThreads) void partition_kernel(Params p)
         p.header[kHdrActive] = active;
         p.header[kHdrSlots] = p.slots;
         p.header[kHdrNonEmpty] = carry.y;
+        p.header[kHdrGroup] = 1;
     }
     // cum_pages was written by other threads of this block: make it visible before searching it
     __threadfence();

@@ -178,11 +178,13 @@ def test_partition_bit_exact(torch_cuda):
             tl = torch.tensor(lens, dtype=torch.int32, device="cuda:0")
             hdr, ws, cum = op.partition(tl)
             slots = jb.jd_wave_slots(op.handle)
-            rh, rws, rcum = partition_ref.partition(lens, hkv, slots, maxp)
-            assert hdr[:4] == rh, (lens[:8], hdr, rh)
+            wg = hdr[4]
+            assert wg == (1 if variant == 1 else min(4, hkv & -hkv))
+            rh, rws, rcum = partition_ref.partition(lens, hkv, slots, maxp, group_waves=wg)
+            assert hdr[:5] == rh, (lens[:8], hdr, rh)
             assert cum == rcum
-            assert ws[:rh[2]] == rws
-            assert all(r == [0, 0, 0, 0] for r in ws[rh[2]:])
+            assert ws[:rh[2] * wg] == rws
+            assert all(r == [0, 0, 0, 0] for r in ws[rh[2] * wg:])
             if max(lens) > maxp * 16:
                 with pytest.raises(jb.JdError):
                     op.check_flags()

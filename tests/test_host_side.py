@@ -80,31 +80,32 @@ def test_schedule_matches_reference():
         assert active <= slots and (active - 1) * span < units <= active * span or units == 0
 
 
-def test_reference_partition_covers_every_page_once():
+@pytest.mark.parametrize("wg", [1, 2])
+def test_reference_partition_covers_every_page_once(wg):
     rng = np.random.default_rng(1)
     lens = np.floor(rng.lognormal(np.log(700.0), 1.2, size=300)).astype(int).clip(0, 9000)
     lens[::17] = 0
     hkv, slots, maxp = 2, 64, 2048
-    hdr, starts, cum = partition_ref.partition(lens, hkv, slots, maxp)
-    segs = partition_ref.segments(lens, hkv, slots, maxp)
+    hdr, starts, cum = partition_ref.partition(lens, hkv, slots, maxp, group_waves=wg)
+    segs = partition_ref.segments(lens, hkv, slots, maxp, group_waves=wg)
     seen = {}
     for w, b, kv, p0, p1 in segs:
-        assert p1 > p0
+        assert p1 > p0 and kv % wg == w % wg
         for pg in range(p0, p1):
             assert (b, kv, pg) not in seen
             seen[(b, kv, pg)] = w
-    assert len(seen) == hdr[0] == sum(partition_ref.pages(int(L), maxp) for L in lens) * hkv
-    # every wave gets the same number of units (the last one the remainder), in line order
-    per_wave = np.bincount([w for w, *_ in segs for _ in range(1)], minlength=hdr[2])
-    units = np.zeros(hdr[2], dtype=int)
+    assert len(seen) == hdr[0] * wg == sum(partition_ref.pages(int(L), maxp) for L in lens) * hkv
+    # every wave gets the same number of pages (the waves of the last group the remainder), in line order
+    nwaves = hdr[2] * wg
+    units = np.zeros(nwaves, dtype=int)
     for w, b, kv, p0, p1 in segs:
         units[w] += p1 - p0
-    assert (units[:-1] == hdr[1]).all() and 0 < units[-1] <= hdr[1] and per_wave.min() >= 1
+    assert (units[:-wg] == hdr[1]).all() and (units[-wg:] == units[-1]).all() and 0 < units[-1] <= hdr[1]
     # the first segment of every wave is where wave_start says it begins
     first = {}
     for w, b, kv, p0, _ in segs:
         first.setdefault(w, [b, kv, p0, 0])
-    assert [first[w] for w in range(hdr[2])] == starts
+    assert [first[w] for w in range(nwaves)] == starts
 
 
 def test_generator_matches_documented_totals():
