@@ -83,7 +83,7 @@ jd_status validate(const jd_config* c, std::string& msg)
         msg = "the vector variant supports group sizes 1, 2, 4, 7 and 8"; return JD_ERR_UNSUPPORTED;
     }
     if (c->variant != JD_VARIANT_VECTOR && c->batch > jd::mfma_max_batch()) {
-        msg = "the matrix-core variant supports batches up to 32768"; return JD_ERR_UNSUPPORTED;
+        msg = "the matrix-core variant supports batches up to 8192"; return JD_ERR_UNSUPPORTED;
     }
     return JD_OK;
 }

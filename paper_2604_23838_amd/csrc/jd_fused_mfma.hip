@@ -85,6 +85,7 @@ struct Geometry {
     static constexpr int kChunksPerRow = kRowBytes / 16;
     static constexpr int kRowsPerLoad = 1024 / kRowBytes;
     static_assert(kWaves * kWaveBytes <= kLdsBudget, "LDS ring does not fit");
+    static_assert(kWaves * kWaveBytes >= (2 * 8192 + 2 * kWaves * 64 + 256) * 4, "ring too small for the prologue tables");
 };
 
 __device__ inline void dma16(unsigned lds_addr, unsigned lane_off, const void* base)
@@ -117,6 +118,7 @@ __device__ inline void wait_stage(int ahead)
 // Producer cursor: the next page-unit to fetch.
 struct Cursor {
     int upos;           // position on the work line
+    int r;              // index of the request among those that own pages
     int b, kv, pg;      // request, kv head, page within the request
     int L, n;           // tokens and pages of request b
     int seg_pg0;        // page at which the current segment began
@@ -206,25 +208,29 @@ struct Wave {
     }
 
     // ---- producer -------------------------------------------------------------------------------
-    // Move to the next request that owns pages (only called while units remain, so one exists).
+    // Move to the next request that owns pages (only called while units remain, so one exists): its id
+    // comes from the compacted list the prologue stored, so finished rows cost nothing here.
     __device__ inline void next_request()
     {
-        int b = cur.b, L = 0, n = 0;
-        do {
-            ++b;
-            if (b >= p.B) {  // seq_lens changed under the kernel: stay in bounds, flag it
-                b = p.B - 1;
-                if (lane == 0) atomicOr(&p.header[kHdrBadInput], 4);
-                L = 1;
-                n = 1;
-                break;
-            }
-            L = uniform_load(p.seq_lens + b);
-            n = pages_of(p, L);
-        } while (n == 0);
+        int r = cur.r + 1;
+        if (r >= live) {  // seq_lens changed under the kernel: stay in bounds, flag it
+            r = live - 1;
+            if (lane == 0) atomicOr(&p.header[kHdrBadInput], 4);
+        }
+        // The list was stored earlier in this kernel, so the compiler will not take it through the scalar
+        // path by itself; a vector load here would make it drain the page ring.  The block's own stores
+        // completed before its first wave got here.
+        int b;
+        asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(b)
+                     : "s"(scalar_ptr(reinterpret_cast<const char*>(p.req) + (static_cast<uint64_t>(static_cast<unsigned>(r)) << 2)))
+                     : "memory");
+        const int L = uniform_load(p.seq_lens + b);
+        int n = pages_of(p, L);
+        if (n == 0) n = 1;  // same cause; a one-page request keeps every index in range
+        cur.r = r;
         cur.b = b;
         cur.n = n;
-        cur.L = L > n * kPage ? n * kPage : L;
+        cur.L = L > n * kPage ? n * kPage : (L < 1 ? 1 : L);
     }
 
     // Describe the unit at the cursor, request its block-table entry, and move the cursor on.
@@ -520,6 +526,7 @@ struct Wave {
     int wave;       // index of this wave
     int member;     // its place in its group of wg waves: it serves the kv heads congruent to member mod wg
     int span;       // group-units per group of waves
+    int live;       // requests that own pages
     int first_bkv, first_n, first_pg0;  // the stream the span begins in, and the page it begins at
 
     template <int S>
@@ -584,43 +591,63 @@ struct Wave {
 constexpr int kThreads = kWaves * 64;
 
 
-// Exclusive prefix of pages per request into s_cum[0..B] (LDS), by all threads of the block.
-__device__ inline void scan_pages(const Params& p, int* s_cum, int* s_part)
+// The partition tables, by all threads of the block: the requests that own pages are compacted, in
+// order, into c_req[0..R) (their ids) and c_cum[0..R] (pages before each, total at the end), both in
+// LDS; the id list is also stored to the workspace (every block stores the same values), where the
+// waves find the next live request when they walk off the end of one.  Returns R.
+__device__ inline int build_tables(const Params& p, int* c_cum, int* c_req, int* s_part)
 {
     const int tid = threadIdx.x;
     const int chunk = (p.B + kThreads - 1) / kThreads;
     const int b0 = min(tid * chunk, p.B), b1 = min(b0 + chunk, p.B);
-    int local = 0;
+    int pages = 0, live = 0;
     for (int b = b0; b < b1; ++b) {
         const int L = p.seq_lens[b];
         if (L > p.maxp * kPage && p.header[kHdrBadInput] == 0) atomicOr(&p.header[kHdrBadInput], 1);
-        local += pages_of(p, L);
+        const int n = pages_of(p, L);
+        pages += n;
+        live += n > 0;
     }
-    s_part[tid] = local;
+    s_part[tid] = pages;
+    s_part[kThreads + tid] = live;
     __syncthreads();
     if (tid < 64) {
         constexpr int per = kThreads / 64;
-        int v[per], sum = 0;
 #pragma unroll
-        for (int i = 0; i < per; ++i) { v[i] = s_part[tid * per + i]; sum += v[i]; }
-        int inc = sum;
+        for (int which = 0; which < 2; ++which) {
+            int* arr = s_part + which * kThreads;
+            int v[per], sum = 0;
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int t = __shfl_up(inc, d, 64);
-            if (tid >= d) inc += t;
+            for (int i = 0; i < per; ++i) { v[i] = arr[tid * per + i]; sum += v[i]; }
+            int inc = sum;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int t = __shfl_up(inc, d, 64);
+                if (tid >= d) inc += t;
+            }
+            int run = inc - sum;
+#pragma unroll
+            for (int i = 0; i < per; ++i) { arr[tid * per + i] = run; run += v[i]; }
         }
-        int run = inc - sum;
-#pragma unroll
-        for (int i = 0; i < per; ++i) { s_part[tid * per + i] = run; run += v[i]; }
     }
     __syncthreads();
-    int run = s_part[tid];
+    int run_p = s_part[tid], run_r = s_part[kThreads + tid];
     for (int b = b0; b < b1; ++b) {
-        s_cum[b] = run;
-        run += pages_of(p, p.seq_lens[b]);
+        const int n = pages_of(p, p.seq_lens[b]);
+        if (n > 0) {
+            c_cum[run_r] = run_p;
+            c_req[run_r] = b;
+            p.req[run_r] = b;
+            ++run_r;
+            run_p += n;
+        }
     }
-    if (b1 == p.B && b0 < b1) s_cum[p.B] = run;
+    if (tid == kThreads - 1) {  // the last thread ends on the totals
+        c_cum[run_r] = run_p;
+        s_part[2 * kThreads] = run_r;
+    }
     __syncthreads();
+    return s_part[2 * kThreads];
 }
 
 template <int D, int QKB, int NS>
@@ -631,100 +658,112 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
 
     JD_STAMP(blockIdx.x * kWaves + (threadIdx.x >> 6), 0);
     // ---- prologue: work partition (the ring doubles as scratch until the first page is fetched) ----
-    int* s_cum = reinterpret_cast<int*>(ring);
-    int* s_part = s_cum + ((p.B + 1 + 63) & ~63);
-    scan_pages(p, s_cum, s_part);
+    int* c_cum = reinterpret_cast<int*>(ring);
+    int* c_req = c_cum + ((p.B + 1 + 63) & ~63);
+    int* s_part = c_req + ((p.B + 63) & ~63);
+    // (values read from LDS are wave-uniform here; saying so keeps everything derived from them on the scalar unit)
+    const int live = __builtin_amdgcn_readfirstlane(build_tables(p, c_cum, c_req, s_part));
     JD_STAMP(blockIdx.x * kWaves + (threadIdx.x >> 6), 1);
     // Waves work in groups of wg: the waves of a group walk the same (request, page) sequence, each on its
     // own kv heads (member, member + wg, ...), so that together they read neighbouring kv heads of the
     // same physical page at about the same time.  The work line is counted in group-units
     // (request, kv-head group, page); a group of waves owns a span of it.
     const int hg = p.Hkv / p.wg;
-    const int units = s_cum[p.B] * hg;
+    const int units = __builtin_amdgcn_readfirstlane(c_cum[live]) * hg;
     const int span = span_for(units, p.slots / p.wg);
     const int active = (units + span - 1) / span;   // groups that own at least one unit
 
     const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * kWaves + wave_in_block);
     const int group = wave / p.wg, member = wave % p.wg;
-    int sb = 0, skv = 0, spg = 0;
+    int sr = 0, sb = 0, skv = 0, spg = 0;
     if (group < active) {
         const int u = group * span;
-        int lo = 0, hi = p.B - 1;  // the last request whose first unit is <= u
+        int lo = 0, hi = live - 1;  // the last live request whose first unit is <= u
         while (lo < hi) {
             const int mid = (lo + hi + 1) >> 1;
-            if (s_cum[mid] * hg <= u) lo = mid; else hi = mid - 1;
+            if (c_cum[mid] * hg <= u) lo = mid; else hi = mid - 1;
         }
-        const int n = s_cum[lo + 1] - s_cum[lo];
-        const int within = u - s_cum[lo] * hg;
-        sb = lo;
+        const int n = c_cum[lo + 1] - c_cum[lo];
+        const int within = u - c_cum[lo] * hg;
+        sr = lo;
+        sb = c_req[lo];
         skv = (within / n) * p.wg + member;
         spg = within % n;
     }
+    sr = __builtin_amdgcn_readfirstlane(sr);
     sb = __builtin_amdgcn_readfirstlane(sb);
     skv = __builtin_amdgcn_readfirstlane(skv);
     spg = __builtin_amdgcn_readfirstlane(spg);
 
-    // the wave's cursor, and the block-table entries of its first pages (their latency overlaps the
-    // rest of the prologue)
+    if (!partition_only) {
+        // rows of requests without tokens
+        for (int b = blockIdx.x; b < p.B; b += gridDim.x) {
+            if (pages_of(p, p.seq_lens[b]) == 0) {
+                float* o = p.out + static_cast<size_t>(b) * p.Hq * D;
+                for (int i = threadIdx.x; i < p.Hq * D; i += kThreads) o[i] = 0.f;
+            }
+        }
+    } else {
+        // tables for inspection
+        if (blockIdx.x == 0) {
+            for (int b = threadIdx.x; b <= p.B; b += kThreads) {
+                int lo = 0, hi = live;  // pages before request b = pages before the first live request at or after b
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (c_req[mid] < b) lo = mid + 1; else hi = mid;
+                }
+                p.cum_pages[b] = c_cum[lo];
+            }
+            if (threadIdx.x == 0) {
+                p.header[kHdrUnits] = units;
+                p.header[kHdrSpan] = span;
+                p.header[kHdrActive] = active;
+                p.header[kHdrSlots] = p.slots;
+                p.header[kHdrGroup] = p.wg;
+            }
+        }
+        if (group < active && (threadIdx.x & 63) == 0) {
+            i32x4 ws = {sb, skv, spg, sb};
+            reinterpret_cast<i32x4*>(p.wave_start)[wave] = ws;
+        }
+    }
+    __syncthreads();  // the scratch is dead from here on, and this block's copy of the request list is stored
+    if (partition_only || group >= active) return;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    JD_STAMP(wave, 2);
+
     W w(p);
     w.lane = threadIdx.x & 63;
     w.wave = wave;
     w.member = member;
     w.span = span;
+    w.live = live;
     w.u0 = group * span;
     w.u1 = min(w.u0 + span, units);
-    if (group < active && !partition_only) {
-        w.cur.upos = w.u0;
-        w.cur.b = sb;
-        w.cur.kv = skv;
-        w.cur.pg = spg;
-        const int L = uniform_load(p.seq_lens + sb);
-        w.cur.n = pages_of(p, L);
-        w.cur.L = L > w.cur.n * kPage ? w.cur.n * kPage : L;
-        w.cur.seg_pg0 = spg;
-        w.cur.seg_at_start = 1;
-        w.cur.last_bkv = sb * p.Hkv + skv;
-        w.cur.last_n = w.cur.n;
-        w.cur.last_a = w.u0 - spg;
-        w.first_bkv = w.cur.last_bkv;
-        w.first_n = w.cur.n;
-        w.first_pg0 = spg;
-        w.begin();
-    }
-
-    // rows of requests without tokens
-    for (int b = blockIdx.x; b < p.B && !partition_only; b += gridDim.x) {
-        if (s_cum[b + 1] == s_cum[b]) {
-            float* o = p.out + static_cast<size_t>(b) * p.Hq * D;
-            for (int i = threadIdx.x; i < p.Hq * D; i += kThreads) o[i] = 0.f;
-        }
-    }
-    // tables for inspection (read back by the host only on request)
-    if (blockIdx.x == 0) {
-        for (int b = threadIdx.x; b <= p.B; b += kThreads) p.cum_pages[b] = s_cum[b];
-        if (threadIdx.x == 0) {
-            p.header[kHdrUnits] = units;
-            p.header[kHdrSpan] = span;
-            p.header[kHdrActive] = active;
-            p.header[kHdrSlots] = p.slots;
-            p.header[kHdrGroup] = p.wg;
-        }
-    }
-    if (group < active && (threadIdx.x & 63) == 0) {
-        i32x4 ws = {sb, skv, spg, sb};
-        reinterpret_cast<i32x4*>(p.wave_start)[wave] = ws;
-    }
     w.lds_ptr = (lds_char*)ring + wave_in_block * W::Geo::kWaveBytes;
     w.lds_wave = static_cast<unsigned>(reinterpret_cast<uintptr_t>(w.lds_ptr));
     w.init_lane_tables();
     w.records = __builtin_amdgcn_make_buffer_rsrc(p.partials, 0, static_cast<int>(2u * p.slots * record_floats(p.G, D) * 4u), 0x00020000);
     w.m = 0.f;
     w.l = 0.f;
-    __syncthreads();  // the scratch is dead from here on
-    if (partition_only || group >= active) return;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    JD_STAMP(wave, 2);
+    w.cur.upos = w.u0;
+    w.cur.r = sr;
+    w.cur.b = sb;
+    w.cur.kv = skv;
+    w.cur.pg = spg;
+    const int L = uniform_load(p.seq_lens + sb);
+    w.cur.n = pages_of(p, L);
+    w.cur.L = L > w.cur.n * kPage ? w.cur.n * kPage : L;
+    w.cur.seg_pg0 = spg;
+    w.cur.seg_at_start = 1;
+    w.cur.last_bkv = sb * p.Hkv + skv;
+    w.cur.last_n = w.cur.n;
+    w.cur.last_a = w.u0 - spg;
+    w.first_bkv = w.cur.last_bkv;
+    w.first_n = w.cur.n;
+    w.first_pg0 = spg;
+    w.begin();
 
     // ---- main loop and epilogue ----
     w.run();
@@ -768,8 +807,8 @@ int mfma_group_waves(int num_kv_heads)
 
 int mfma_max_batch()
 {
-    // the prologue keeps B + 1 prefix entries and one entry per thread in the smallest ring
-    return 32768;
+    // the prologue keeps 2B + 1 table entries and two entries per thread in the ring (at least 96 KiB)
+    return 8192;
 }
 
 hipError_t launch_fused_mfma(const Params& p, hipStream_t stream, int partition_only)

@@ -114,6 +114,17 @@ def test_wide_batch_of_short_requests(torch_cuda, jo, variant):
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
+def test_stragglers_scattered_in_a_finished_batch(torch_cuda, jo, variant):
+    # a big batch in which all but a few requests have finished: the walk from one live request to the next
+    # crosses long runs of empty rows
+    lens = np.zeros(3000, dtype=np.int32)
+    lens[[0, 1, 70, 1029, 1030, 2998]] = [5000, 33, 7000, 16, 4097, 9000]
+    w = W.build(W.SHAPES[2], lens, seed=13, cfg=99)
+    ref = jo.decode_attention(*arrays(w))
+    check(run_gpu(torch_cuda, arrays(w), variant), ref, f"scattered stragglers v{variant}")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
 def test_scale_override_and_sharp_softmax(torch_cuda, jo, variant):
     # large scale: the softmax is dominated by a few tokens; exercises the running-max rescale
     w = W.gen_config(1, 3)
