@@ -695,6 +695,11 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
     sb = __builtin_amdgcn_readfirstlane(sb);
     skv = __builtin_amdgcn_readfirstlane(skv);
     spg = __builtin_amdgcn_readfirstlane(spg);
+    // Touch the block-table line and the length this wave starts with now: the first access is a cold miss
+    // all the way to HBM, and the rest of the prologue hides it.
+    int warm = 0;
+    if (group < active && !partition_only)
+        warm = uniform_load(p.block_table + static_cast<size_t>(sb) * p.maxp + spg) ^ uniform_load(p.seq_lens + sb);
 
     if (!partition_only) {
         // rows of requests without tokens
@@ -730,7 +735,7 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
     }
     __syncthreads();  // the scratch is dead from here on, and this block's copy of the request list is stored
     if (partition_only || group >= active) return;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(0)" :: "s"(warm) : "memory");
     JD_STAMP(wave, 2);
 
     W w(p);

@@ -214,6 +214,34 @@ def test_bad_page_id_is_flagged_not_dereferenced(torch_cuda):
         assert e.value.status == jb.JD_ERR_BAD_INPUT
 
 
+def test_random_shapes(torch_cuda, jo):
+    # a seeded sweep over head layouts, group sizes up to 16, both head sizes and mixed length patterns
+    rng = np.random.default_rng(2024)
+    heads = [(1, 1), (2, 1), (3, 1), (5, 5), (6, 2), (8, 8), (12, 4), (16, 2), (16, 1), (24, 8), (40, 8), (48, 16), (64, 4)]
+    for case in range(36):
+        Hq, Hkv = heads[rng.integers(len(heads))]
+        D = int(rng.choice([64, 128]))
+        B = int(rng.integers(1, 40))
+        kind = case % 4
+        if kind == 0:
+            lens = rng.integers(0, 40, size=B)
+        elif kind == 1:
+            lens = np.floor(rng.lognormal(np.log(300.0), 1.5, size=B)).clip(0, 12000)
+        elif kind == 2:
+            lens = rng.choice([0, 1, 15, 16, 17, 255, 256, 257, 4095], size=B)
+        else:
+            lens = np.where(rng.random(B) < 0.8, 0, rng.integers(1, 6000, size=B))
+        lens = lens.astype(np.int32)
+        shp = W.Shape(f"rand{case}", B, Hq, Hkv, D, 1)
+        w = W.build(shp, lens, seed=case, cfg=200 + case)
+        ref = jo.decode_attention(*arrays(w))
+        G = Hq // Hkv
+        for variant in ((1, 2) if G in (1, 2, 4, 7, 8) else (2,)):
+            budget = int(rng.choice([0, 0, 2, 33]))
+            print(f"case {case}: B={B} Hq={Hq} Hkv={Hkv} D={D} kind={kind} variant={variant} budget={budget}", flush=True)
+            check(run_gpu(torch_cuda, arrays(w), variant, cu_budget=budget), ref, f"random case {case} v{variant}")
+
+
 def _to_dev(torch, arrs):
     dev = torch.device("cuda:0")
     q, kp, vp, bt, lens = arrs
