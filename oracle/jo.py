@@ -40,6 +40,9 @@ def load_library(path: str):
     lib.jo_partial_state.restype = C.c_int
     lib.jo_merge_states.argtypes = [C.c_int, p, p, p, C.c_int, p]
     lib.jo_merge_states.restype = C.c_int
+    lib.jo_prefill_attention.argtypes = [p, p, p, p, p, p, p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                         C.c_int, C.c_double, p, p, C.c_int]
+    lib.jo_prefill_attention.restype = C.c_int
     lib.jo_max_threads.restype = C.c_int
     return lib
 
@@ -123,6 +126,35 @@ def merge_states(ms, ls, accs):
     if _load().jo_merge_states(ms.size, _ptr(ms), _ptr(ls), _ptr(accs), accs.shape[1], _ptr(out)):
         raise ValueError("jo_merge_states: malformed arguments")
     return out
+
+
+def prefill_attention(q, k_pages, v_pages, block_table, seq_lens, q_lens, q_offsets, *, scale=0.0, threads=0,
+                      want64=False):
+    """Causal attention of each request's last q_lens[b] tokens over its paged cache.
+
+    q is [TQ, Hq, D] (bf16 bits); request b's new tokens are rows q_offsets[b] .. q_offsets[b]+q_lens[b]-1.
+    Returns float32 [TQ, Hq, D] (rows no request owns are zero); with want64 also the float64 array."""
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    k_pages = np.ascontiguousarray(k_pages, dtype=np.uint16)
+    v_pages = np.ascontiguousarray(v_pages, dtype=np.uint16)
+    block_table = np.ascontiguousarray(block_table, dtype=np.int32)
+    seq_lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    q_lens = np.ascontiguousarray(q_lens, dtype=np.int32)
+    q_offsets = np.ascontiguousarray(q_offsets, dtype=np.int32)
+    TQ, Hq, D = q.shape
+    NP, Hkv, page, _ = k_pages.shape
+    B = seq_lens.shape[0]
+    assert q_lens.shape == (B,) and q_offsets.shape[0] >= B and block_table.shape[0] == B
+    if B and int(q_offsets[B - 1]) + int(q_lens[B - 1]) > TQ:
+        raise ValueError("jo_prefill_attention: q has fewer rows than the offsets and lengths address")
+    o32 = np.zeros((TQ, Hq, D), dtype=np.float32)
+    o64 = np.zeros((TQ, Hq, D), dtype=np.float64) if want64 else None
+    rc = _load().jo_prefill_attention(_ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table), _ptr(seq_lens),
+                                      _ptr(q_lens), _ptr(q_offsets), B, Hq, Hkv, D, page, block_table.shape[1],
+                                      float(scale), _ptr(o64), _ptr(o32), int(threads))
+    if rc:
+        raise ValueError("jo_prefill_attention: malformed arguments")
+    return (o32, o64) if want64 else o32
 
 
 def max_threads() -> int:

@@ -260,6 +260,89 @@ int jo_merge_states(int n, const double *m, const double *l, const double *acc, 
     return 0;
 }
 
+/*
+ * Causal attention of a chunk of new tokens over the paged cache (prefill / KV recomputation).
+ * Request b has L = seq_lens[b] tokens in the cache, the last n = q_lens[b] of which are the new ones;
+ * their queries are rows q_offsets[b] .. q_offsets[b] + n - 1 of q ([TQ, Hq, D]).  New token t
+ * (0 <= t < n) sits at position c + t with c = L - n and attends to positions 0 .. c + t:
+ *
+ *     out[q_offsets[b] + t][h] = sum_{j <= c + t} softmax_j(scale * <q_t,h , K_j>) V_j
+ *
+ * This is what a migrated request pays to rebuild its cache (Sub-stage Merging: the migration
+ * overhead is dominated by KV cache recomputation), and what every new turn of a multi-turn
+ * rollout starts with (Motivation, "Multi-turn Rollout Idling").  With n = 1 it is exactly
+ * jo_decode_attention.  Outputs are [TQ, Hq, D]; out64 / out32 may be NULL.  Returns 0, or 1 on a
+ * malformed argument (n < 0, n > L, offsets not increasing by at least n).
+ */
+int jo_prefill_attention(const uint16_t *q, const uint16_t *k_pages, const uint16_t *v_pages,
+                         const int32_t *block_table, const int32_t *seq_lens, const int32_t *q_lens,
+                         const int32_t *q_offsets, int B, int Hq, int Hkv, int D, int page_size,
+                         int max_pages_per_seq, double scale, double *out64, float *out32, int threads)
+{
+    jo_problem p = { q, k_pages, v_pages, block_table, seq_lens, B, Hq, Hkv, D, page_size,
+                     max_pages_per_seq, resolve_scale(scale, D) };
+    if (check(&p) || !q_lens || !q_offsets)
+        return 1;
+    for (int b = 0; b < B; ++b) {
+        int L = seq_lens[b] > 0 ? seq_lens[b] : 0;
+        if (q_lens[b] < 0 || q_lens[b] > L || q_offsets[b] < 0)
+            return 1;
+        if (b + 1 < B && q_offsets[b + 1] < q_offsets[b] + q_lens[b])
+            return 1;
+    }
+#ifdef _OPENMP
+    if (threads > 0)
+        omp_set_num_threads(threads);
+#endif
+    (void)threads;
+    int G = Hq / Hkv;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < Hq; ++h) {
+            int L = seq_lens[b] > 0 ? seq_lens[b] : 0;
+            int n = q_lens[b], c = L - n, kv = h / G;
+            double *w = (double *)malloc(sizeof(double) * (size_t)(L + 1));
+            double *acc = (double *)malloc(sizeof(double) * (size_t)D);
+            for (int t = 0; t < n; ++t) {
+                int64_t row = (int64_t)q_offsets[b] + t;
+                const uint16_t *qr = q + (row * Hq + h) * D;
+                int last = c + t; /* attends to positions 0 .. last */
+                double m = -INFINITY, z = 0.0;
+                for (int j = 0; j <= last; ++j) {
+                    const uint16_t *kr = token_row(&p, k_pages, b, kv, j);
+                    double s = 0.0;
+                    for (int d = 0; d < D; ++d)
+                        s += bf16_to_f64(qr[d]) * bf16_to_f64(kr[d]);
+                    w[j] = p.scale * s;
+                    if (w[j] > m)
+                        m = w[j];
+                }
+                for (int j = 0; j <= last; ++j) {
+                    w[j] = exp(w[j] - m);
+                    z += w[j];
+                }
+                for (int d = 0; d < D; ++d)
+                    acc[d] = 0.0;
+                for (int j = 0; j <= last; ++j) {
+                    const uint16_t *vr = token_row(&p, v_pages, b, kv, j);
+                    double wj = w[j] / z;
+                    for (int d = 0; d < D; ++d)
+                        acc[d] += wj * bf16_to_f64(vr[d]);
+                }
+                for (int d = 0; d < D; ++d) {
+                    if (out64)
+                        out64[(row * Hq + h) * D + d] = acc[d];
+                    if (out32)
+                        out32[(row * Hq + h) * D + d] = (float)acc[d];
+                }
+            }
+            free(w);
+            free(acc);
+        }
+    }
+    return 0;
+}
+
 int jo_max_threads(void)
 {
 #ifdef _OPENMP
