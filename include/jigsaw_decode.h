@@ -130,6 +130,29 @@ jd_status jd_append_kv(jd_handle *h, const void *k_new, const void *v_new, void 
                        const int32_t *block_table, int32_t *seq_lens, const int32_t *active, void *stream);
 
 /*
+ * Causal attention of a chunk of new tokens over the paged cache: prefill of a prompt or of a new
+ * turn, and the KV recomputation a migrated request pays (Sub-stage Merging: the migration overhead
+ * is dominated by KV cache recomputation; Motivation, "Multi-turn Rollout Idling": new turns trigger
+ * additional prefill).  Request b has L = seq_lens[b] tokens in the cache, the last n = q_lens[b]
+ * of which are the new ones (their K/V are already in place); new token t sits at position
+ * L - n + t and attends to positions 0 .. L - n + t.
+ *   q           bf16 [TQ, Hq, D]           device, 16-byte aligned, read; request b's new tokens are rows
+ *                                          q_offsets[b] .. q_offsets[b] + n - 1
+ *   k_pages, v_pages, block_table, seq_lens   as for jd_decode_attention
+ *   q_lens      int32 [B]                  device, read; 0 = nothing to do for the request; values above L
+ *                                          are clamped to L
+ *   q_offsets   int32 [B]                  device, read; the rows of different requests must not overlap
+ *   max_q_len   host value: an upper bound of q_lens (it sizes the launch; tokens beyond it are not computed)
+ *   out         fp32 [TQ, Hq, D]           device, 16-byte aligned; the rows of the new tokens are written,
+ *                                          all others are left untouched
+ * With n = 1 for every request the result is that of jd_decode_attention.  Only enqueues on `stream`.
+ * Bound by the matrix cores rather than by HBM; same input checks and flags as jd_decode_attention.
+ */
+jd_status jd_prefill_attention(jd_handle *h, const void *q, const void *k_pages, const void *v_pages,
+                               const int32_t *block_table, const int32_t *seq_lens, const int32_t *q_lens,
+                               const int32_t *q_offsets, int32_t max_q_len, float *out, void *stream);
+
+/*
  * Synchronise `stream` and report device-side input checks of the calls completed so far:
  * JD_OK, JD_ERR_BAD_INPUT (and clears the flag) or JD_ERR_HIP.
  */

@@ -17,6 +17,7 @@ JD_OK, JD_ERR_INVALID_ARG, JD_ERR_UNSUPPORTED, JD_ERR_HIP, JD_ERR_BAD_INPUT = ra
 JD_VARIANT_DEFAULT, JD_VARIANT_VECTOR, JD_VARIANT_MFMA = range(3)
 
 EXPORTS = ("jd_validate_config", "jd_workspace_bytes", "jd_create", "jd_decode_attention", "jd_append_kv",
+           "jd_prefill_attention",
            "jd_check_device_flags", "jd_debug_partition", "jd_profile_enable", "jd_profile_read",
            "jd_debug_stream_read", "jd_debug_stream_copy",
            "jd_debug_schedule", "jd_wave_slots", "jd_destroy",
@@ -58,6 +59,8 @@ def lib():
         l.jd_decode_attention.restype = C.c_int
         l.jd_append_kv.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
         l.jd_append_kv.restype = C.c_int
+        l.jd_prefill_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_int32, vp, vp]
+        l.jd_prefill_attention.restype = C.c_int
         l.jd_check_device_flags.argtypes = [vp, vp]
         l.jd_check_device_flags.restype = C.c_int
         l.jd_debug_partition.argtypes = [vp, vp, vp, vp, vp, vp]
@@ -112,6 +115,15 @@ def jd_decode_attention(handle, q, k_pages, v_pages, block_table, seq_lens, out,
 def jd_append_kv(handle, k_new, v_new, k_pages, v_pages, block_table, seq_lens, active=None, stream=0) -> None:
     """Device addresses (ints); `active` may be None."""
     st = lib().jd_append_kv(handle, k_new, v_new, k_pages, v_pages, block_table, seq_lens, active, stream)
+    if st != JD_OK:
+        raise JdError(st, jd_last_error_string(handle))
+
+
+def jd_prefill_attention(handle, q, k_pages, v_pages, block_table, seq_lens, q_lens, q_offsets, max_q_len, out,
+                         stream=0) -> None:
+    """Device addresses (ints); max_q_len is a host integer."""
+    st = lib().jd_prefill_attention(handle, q, k_pages, v_pages, block_table, seq_lens, q_lens, q_offsets,
+                                    int(max_q_len), out, stream)
     if st != JD_OK:
         raise JdError(st, jd_last_error_string(handle))
 
@@ -235,6 +247,26 @@ class DecodeAttention:
         jd_append_kv(self.handle, k_new.data_ptr(), v_new.data_ptr(), k_pages.data_ptr(), v_pages.data_ptr(),
                      block_table.data_ptr(), seq_lens.data_ptr(), None if active is None else active.data_ptr(),
                      s.cuda_stream)
+
+    def prefill(self, q, k_pages, v_pages, block_table, seq_lens, q_lens, q_offsets, max_q_len, out=None, stream=None):
+        """Causal attention of each request's last q_lens[b] tokens; q is bf16 [TQ, Hq, D], out fp32 [TQ, Hq, D]."""
+        import torch
+        c = self.cfg
+        if not (q.is_cuda and q.dtype == torch.bfloat16 and q.dim() == 3 and tuple(q.shape[1:]) == (c.num_q_heads, c.head_dim)
+                and q.is_contiguous()):
+            raise ValueError("q must be a contiguous CUDA bf16 [TQ, Hq, D] tensor")
+        for t in (q_lens, q_offsets):
+            if not (t.is_cuda and t.dtype == torch.int32 and t.dim() == 1 and t.shape[0] >= c.batch):
+                raise ValueError("q_lens / q_offsets must be CUDA int32 [B] tensors")
+        if out is None:
+            out = torch.zeros(q.shape, dtype=torch.float32, device=q.device)
+        if not (out.is_cuda and out.dtype == torch.float32 and tuple(out.shape) == tuple(q.shape) and out.is_contiguous()):
+            raise ValueError("out must be a contiguous CUDA float32 tensor shaped like q")
+        s = torch.cuda.current_stream() if stream is None else stream
+        jd_prefill_attention(self.handle, q.data_ptr(), k_pages.data_ptr(), v_pages.data_ptr(), block_table.data_ptr(),
+                             seq_lens.data_ptr(), q_lens.data_ptr(), q_offsets.data_ptr(), max_q_len, out.data_ptr(),
+                             s.cuda_stream)
+        return out
 
     def check_flags(self, stream=None):
         import torch

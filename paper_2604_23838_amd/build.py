@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libjigsaw_decode.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["jd_api.hip", "jd_partition.hip", "jd_partial_vector.hip", "jd_fused_mfma.hip", "jd_combine.hip", "jd_append.hip",
+SOURCES = ["jd_api.hip", "jd_partition.hip", "jd_partial_vector.hip", "jd_fused_mfma.hip", "jd_combine.hip", "jd_append.hip", "jd_prefill.hip",
            "jd_stream_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument",
          # packed fp32 instructions are kept out of every kernel of this library

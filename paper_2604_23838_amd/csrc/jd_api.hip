@@ -227,6 +227,27 @@ jd_status jd_append_kv(jd_handle* h, const void* k_new, const void* v_new, void*
     return JD_OK;
 }
 
+jd_status jd_prefill_attention(jd_handle* h, const void* q, const void* k_pages, const void* v_pages,
+                               const int32_t* block_table, const int32_t* seq_lens, const int32_t* q_lens,
+                               const int32_t* q_offsets, int32_t max_q_len, float* out, void* stream)
+{
+    if (!h) return fail(nullptr, JD_ERR_INVALID_ARG, "handle is NULL");
+    if (!q || !k_pages || !v_pages || !block_table || !seq_lens || !q_lens || !q_offsets || !out)
+        return fail(h, JD_ERR_INVALID_ARG, "q, k_pages, v_pages, block_table, seq_lens, q_lens, q_offsets and out must be non-NULL");
+    if (misaligned(q) || misaligned(k_pages) || misaligned(v_pages) || misaligned(out))
+        return fail(h, JD_ERR_INVALID_ARG, "q, k_pages, v_pages and out must be 16-byte aligned");
+    if (max_q_len < 0) return fail(h, JD_ERR_INVALID_ARG, "max_q_len must be >= 0");
+    jd::Params p = h->params;
+    p.k_pages = static_cast<const uint16_t*>(k_pages);
+    p.v_pages = static_cast<const uint16_t*>(v_pages);
+    p.block_table = block_table;
+    p.seq_lens = seq_lens;
+    hipError_t e = jd::launch_prefill(p, static_cast<const uint16_t*>(q), q_lens, q_offsets, max_q_len, out,
+                                      static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(h, JD_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
+    return JD_OK;
+}
+
 jd_status jd_check_device_flags(jd_handle* h, void* stream)
 {
     if (!h) return fail(nullptr, JD_ERR_INVALID_ARG, "handle is NULL");

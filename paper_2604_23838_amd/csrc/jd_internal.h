@@ -62,6 +62,10 @@ hipError_t launch_combine(const Params& p, hipStream_t stream);
 hipError_t launch_append_kv(const Params& p, const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pages,
                             uint16_t* v_pages, int32_t* seq_lens, const int32_t* active, hipStream_t stream);
 
+hipError_t launch_prefill(const Params& p, const uint16_t* q, const int32_t* q_lens, const int32_t* q_offsets,
+                          int max_q_len, float* out, hipStream_t stream);
+int prefill_block_tokens(int G, int D);
+
 // Wave slots each variant wants per compute unit.
 int vector_waves_per_cu();
 int mfma_waves_per_cu();

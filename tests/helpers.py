@@ -52,3 +52,13 @@ def error_report(got, ref, floor=1e-3):
     ref = np.asarray(ref, dtype=np.float64)
     diff = np.abs(got - ref)
     return float(diff.max(initial=0.0)), float((diff / np.maximum(np.abs(ref), floor)).max(initial=0.0))
+
+
+def prefill_inputs(w, q_lens, seed=0):
+    """Packed queries for the last q_lens[b] tokens of every request of workload w."""
+    rng = np.random.default_rng(seed)
+    q_lens = np.asarray(q_lens, dtype=np.int32)
+    offs = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32)
+    s = w.shape
+    q = W.f32_to_bf16_bits(rng.standard_normal((int(offs[-1]) + 3, s.num_q_heads, s.head_dim), dtype=np.float32))
+    return q, q_lens, offs

@@ -1,0 +1,116 @@
+"""GPU parity of jd_prefill_attention (causal attention of new tokens over the paged cache) against the fp64
+oracle, element by element, to the decode path's tolerance (max-abs 5e-3, max-rel 1e-2 above the floor)."""
+import numpy as np
+import pytest
+
+from paper_2604_23838_amd import workloads as W
+from helpers import error_report, prefill_inputs
+
+pytestmark = pytest.mark.gpu
+
+ABS_TOL, REL_TOL = 5e-3, 1e-2
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    return torch
+
+
+def bf16_dev(torch, a):
+    return torch.from_numpy(a.view(np.int16)).to("cuda:0").view(torch.bfloat16)
+
+
+def run_prefill(torch, w, q, q_lens, offs, max_q_len=None, scale=0.0):
+    from paper_2604_23838_amd import binding as jb
+    s = w.shape
+    op = jb.DecodeAttention(s.batch, s.num_q_heads, s.num_kv_heads, s.head_dim, w.max_pages_per_seq, w.num_pages,
+                            softmax_scale=scale)
+    out = torch.full(q.shape, 777.0, dtype=torch.float32, device="cuda:0")     # sentinel: unowned rows stay put
+    op.prefill(bf16_dev(torch, q), bf16_dev(torch, w.k_pages), bf16_dev(torch, w.v_pages),
+               torch.from_numpy(w.block_table).to("cuda:0"), torch.from_numpy(w.seq_lens).to("cuda:0"),
+               torch.from_numpy(np.asarray(q_lens, dtype=np.int32)).to("cuda:0"),
+               torch.from_numpy(np.asarray(offs, dtype=np.int32)).to("cuda:0"),
+               int(max(q_lens)) if max_q_len is None else max_q_len, out=out)
+    torch.cuda.synchronize()
+    op.check_flags()
+    op.close()
+    return out.cpu().numpy()
+
+
+def check(got, ref, q_lens, offs):
+    owned = np.zeros(got.shape[0], dtype=bool)
+    for b, n in enumerate(q_lens):
+        owned[offs[b]:offs[b] + n] = True
+    assert np.all(got[~owned] == 777.0), "rows of no request were written"
+    if owned.any():
+        assert np.isfinite(got[owned]).all()
+        ma, mr = error_report(got[owned], ref[owned])
+        assert ma <= ABS_TOL and mr <= REL_TOL, (ma, mr)
+
+
+SHAPES = [(8, 2, 64), (32, 8, 128), (14, 2, 64), (64, 8, 128), (16, 1, 64), (12, 4, 128), (4, 4, 128)]
+
+
+@pytest.mark.parametrize("hq,hkv,d", SHAPES)
+def test_chunks_after_a_context_and_full_prefills(torch_cuda, jo, hq, hkv, d):
+    shp = W.Shape("t", 0, hq, hkv, d, 1)
+    lens = np.array([17, 100, 250, 1000, 16, 1, 333, 48, 5], dtype=np.int32)
+    # full prefill, chunk after a context, nothing to do, one token (= decode), ragged tails, page-aligned
+    ql = np.array([17, 33, 0, 257, 16, 1, 1, 32, 3], dtype=np.int32)
+    w = W.build(shp, lens, seed=5, cfg=81)
+    q, ql, offs = prefill_inputs(w, ql, seed=6)
+    ref = jo.prefill_attention(q, w.k_pages, w.v_pages, w.block_table, w.seq_lens, ql, offs)
+    got = run_prefill(torch_cuda, w, q, ql, offs)
+    check(got, ref, ql, offs)
+
+
+def test_single_new_token_equals_the_decode_entry_point(torch_cuda, jo):
+    from paper_2604_23838_amd import binding as jb
+    torch = torch_cuda
+    w = W.gen_config(1, 3)
+    s = w.shape
+    ql = np.ones(s.batch, dtype=np.int32)
+    offs = np.arange(s.batch, dtype=np.int32)
+    got = run_prefill(torch, w, w.q, ql, offs)
+    op = jb.DecodeAttention(s.batch, s.num_q_heads, s.num_kv_heads, s.head_dim, w.max_pages_per_seq, w.num_pages)
+    dec = op(bf16_dev(torch, w.q), bf16_dev(torch, w.k_pages), bf16_dev(torch, w.v_pages),
+             torch.from_numpy(w.block_table).to("cuda:0"), torch.from_numpy(w.seq_lens).to("cuda:0"))
+    torch.cuda.synchronize()
+    ref = jo.decode_attention(w.q, w.k_pages, w.v_pages, w.block_table, w.seq_lens)
+    check(got, ref, ql, offs)
+    assert np.abs(got - dec.cpu().numpy()).max() <= 1e-5
+
+
+def test_long_prefill_spans_many_query_blocks(torch_cuda, jo):
+    shp = W.Shape("t", 0, 32, 8, 128, 1)
+    lens = np.array([3000, 1111, 4097], dtype=np.int32)
+    ql = np.array([3000, 600, 1025], dtype=np.int32)
+    w = W.build(shp, lens, seed=9, cfg=82)
+    q, ql, offs = prefill_inputs(w, ql, seed=10)
+    ref = jo.prefill_attention(q, w.k_pages, w.v_pages, w.block_table, w.seq_lens, ql, offs)
+    got = run_prefill(torch_cuda, w, q, ql, offs)
+    check(got, ref, ql, offs)
+
+
+def test_scale_override_and_bound_on_query_length(torch_cuda, jo):
+    shp = W.Shape("t", 0, 8, 2, 64, 1)
+    lens = np.array([200, 90], dtype=np.int32)
+    ql = np.array([120, 90], dtype=np.int32)
+    w = W.build(shp, lens, seed=11, cfg=83)
+    q, ql, offs = prefill_inputs(w, ql, seed=12)
+    ref = jo.prefill_attention(q, w.k_pages, w.v_pages, w.block_table, w.seq_lens, ql, offs, scale=0.2)
+    got = run_prefill(torch_cuda, w, q, ql, offs, max_q_len=4096, scale=0.2)     # a loose bound is fine
+    check(got, ref, ql, offs)
+
+
+def test_no_new_tokens_writes_nothing(torch_cuda, jo):
+    shp = W.Shape("t", 0, 8, 2, 64, 1)
+    w = W.build(shp, np.array([40, 0, 7], dtype=np.int32), seed=13, cfg=84)
+    q, ql, offs = prefill_inputs(w, [0, 0, 0], seed=14)
+    got = run_prefill(torch_cuda, w, q, ql, offs, max_q_len=0)
+    assert np.all(got == 777.0)
+    got = run_prefill(torch_cuda, w, q, ql, offs, max_q_len=64)
+    assert np.all(got == 777.0)

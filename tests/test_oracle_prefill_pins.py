@@ -3,17 +3,7 @@ import numpy as np
 import pytest
 
 from paper_2604_23838_amd import workloads as W
-from helpers import gather_contiguous, pack_paged
-
-
-def prefill_inputs(w, q_lens, seed=0):
-    """Packed queries for the last q_lens[b] tokens of every request of workload w."""
-    rng = np.random.default_rng(seed)
-    q_lens = np.asarray(q_lens, dtype=np.int32)
-    offs = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32)
-    s = w.shape
-    q = W.f32_to_bf16_bits(rng.standard_normal((int(offs[-1]) + 3, s.num_q_heads, s.head_dim), dtype=np.float32))
-    return q, q_lens, offs
+from helpers import gather_contiguous, pack_paged, prefill_inputs
 
 
 def test_single_new_token_is_decode_attention(jo):
