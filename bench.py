@@ -14,6 +14,7 @@ fp64 CPU oracle timed on the host cores on a bounded sample of the same workload
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -34,11 +35,12 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--variant", type=int, default=0, help="0 default, 1 vector, 2 mfma")
     ap.add_argument("--cu-budget", type=int, default=0)
-    ap.add_argument("--sweep", choices=["none", "cu", "batch", "loop"], default="none",
+    ap.add_argument("--sweep", choices=["none", "cu", "batch", "loop", "prefill"], default="none",
                     help="extra measurements after the timed region: 'cu' = step time at 25/50/75/100 %% of the "
                          "compute units (the library's cu_budget), 'batch' = step time as the batch shrinks to its "
                          "longest requests, 'loop' = the closed decode loop (KV append + attention) eager and as a replayed "
-                         "HIP graph")
+                         "HIP graph, 'prefill' = causal prefill over the paged cache (KV recomputation of migrated requests, "
+                         "a new turn after a context) against the matrix-core peak")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="CPU-seconds budget of the oracle sample")
     args = ap.parse_args()
@@ -244,6 +246,52 @@ def main() -> int:
                                  "append_bytes": 4 * s.batch * s.num_kv_heads * s.head_dim * 2,
                                  "note": "the K/V pool now holds 64 synthetic tokens per request: parity check skipped"}
         args.no_cpu_baseline = True
+
+    if args.sweep == "prefill":
+        # KV recomputation after a migration and the prefill of a new turn (Sub-stage Merging; Motivation,
+        # "Multi-turn Rollout Idling"), on this config's head shape and length distribution
+        MFMA_PEAK_TFLOPS = 2500.0   # dense bf16
+        rows = []
+        nreq = min(32, s.batch)
+        base = w.seq_lens[:nreq].astype(np.int64)
+        for name, lens_p, ql_p in (("recompute_whole_request", base, base),
+                                    ("new_turn_512_after_context", base + 512, np.full(nreq, 512, dtype=np.int64))):
+            wp = W.build(dataclasses.replace(s, batch=nreq), lens_p.astype(np.int32), seed=args.seed + 1, cfg=70,
+                         threads=min(16, os.cpu_count() or 8))
+            offs = np.concatenate([[0], np.cumsum(ql_p)[:-1]]).astype(np.int32)
+            tq = int(ql_p.sum())
+            qp = torch.randn((tq, s.num_q_heads, s.head_dim), device=dev).bfloat16()
+            kpp = torch.from_numpy(wp.k_pages.view(np.int16)).to(dev).view(torch.bfloat16)
+            vpp = torch.from_numpy(wp.v_pages.view(np.int16)).to(dev).view(torch.bfloat16)
+            btp = torch.from_numpy(wp.block_table).to(dev)
+            slp = torch.from_numpy(wp.seq_lens).to(dev)
+            qlp = torch.from_numpy(ql_p.astype(np.int32)).to(dev)
+            ofp = torch.from_numpy(offs).to(dev)
+            outp = torch.empty((tq, s.num_q_heads, s.head_dim), dtype=torch.float32, device=dev)
+            o2 = jb.DecodeAttention(nreq, s.num_q_heads, s.num_kv_heads, s.head_dim, wp.max_pages_per_seq, wp.num_pages)
+            reps = 10
+            with torch.cuda.stream(stream):
+                for _ in range(2):
+                    o2.prefill(qp, kpp, vpp, btp, slp, qlp, ofp, int(ql_p.max()), out=outp)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(reps):
+                    o2.prefill(qp, kpp, vpp, btp, slp, qlp, ofp, int(ql_p.max()), out=outp)
+                e1.record(stream)
+                torch.cuda.synchronize()
+            o2.check_flags()
+            o2.close()
+            ms = e0.elapsed_time(e1) / reps
+            ctx = lens_p - ql_p
+            pairs = int((ql_p * ctx + ql_p * (ql_p + 1) // 2).sum())      # (query, key) pairs under the causal mask
+            flops = 4.0 * s.num_q_heads * s.head_dim * pairs
+            rows.append({"case": name, "requests": nreq, "new_tokens": tq, "kv_tokens": int(lens_p.sum()),
+                         "ms": round(ms, 4), "new_tokens_per_s": round(tq / ms * 1e3, 1),
+                         "roofline": {"bound": "mfma", "achieved": round(flops / ms / 1e9, 2), "peak": MFMA_PEAK_TFLOPS,
+                                      "unit": "TFLOP/s", "frac": round(flops / ms / 1e9 / MFMA_PEAK_TFLOPS, 4),
+                                      "traffic": None}})
+            del kpp, vpp, qp, outp
+        result["prefill_sweep"] = rows
 
     if not args.no_cpu_baseline:
         from oracle import jo
