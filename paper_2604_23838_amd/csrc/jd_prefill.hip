@@ -2,16 +2,20 @@
 // multi-turn rollout): the last q_lens[b] tokens of request b attend to everything before them and to
 // each other causally.  Unlike decode this is bound by the matrix cores, not by HBM.
 //
-// One block serves one (request, kv head, block of query tokens).  Its kNW waves each hold kNT
-// tiles of 16 query rows in registers (a row is a (token, query head of the group) pair, the group
-// padded to a power of two), and all of them sweep the same K/V pages, which the block stages in a
-// shared LDS ring of 64-key stages with direct loads (each wave issues its share of a stage; one
-// barrier and one softmax update per stage).  Per page and tile the arithmetic is the decode kernel's:
-//   S^T[token][row] = K . Q^T (v_mfma_f32_16x16x32_bf16), online softmax in the exp2 domain,
-//   O^T[d][row]    += V^T . P^T (v_mfma_f32_16x16x32_bf16 over two pages at once, P as bf16 head + bf16 remainder),
-// with V read transposed from LDS.  Keys after a row's own position are excluded by selection; pages
-// wholly above the block's last position are never fetched, pages wholly above a wave's last
-// position are skipped by that wave.  Query blocks of a request are launched heaviest first.
+// One block of kNW waves serves one (request, kv head, block of query tokens); two blocks share a
+// compute unit, so that one's matrix work runs while the other's softmax arithmetic does.  Each wave
+// holds NT tiles of 16 query rows in registers (a row is a (token, query head of the group) pair, the
+// group padded to a power of two), and all waves sweep the same K/V pages, which the block stages in
+// shared LDS rings of 64-key stages with direct loads (each wave issues its share of a stage; one
+// barrier and one softmax update per stage).  The block table reaches LDS the same way, a window of
+// 64 page ids at a time, so no round waits for a table read.  Per stage and tile:
+//   S^T[key][row]  = K . Q^T (v_mfma_f32_16x16x32_bf16), online softmax in the exp2 domain,
+//   O^T[d][row]   += V^T . P^T (same instruction over two pages at once: the 8 keys a lane holds of a
+//                    page pair are one k-group of the 32-deep contraction; P as bf16 head + bf16 remainder),
+//   l[row]        += 1 . P^T   (row sums from the matrix unit, V^T replaced by ones),
+// with V read transposed from LDS.  Keys after a row's own position are excluded by selection (only
+// in the rounds that reach the diagonal); pages wholly above the block's last position are never
+// fetched.  Query blocks of a request are launched heaviest first.
 #include "jd_internal.h"
 #include "jd_walk.h"
 
@@ -28,14 +32,18 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) char lds_char;
 
-constexpr int kNW = 4;   // waves per block (two blocks share a compute unit and drift out of step, so that one's
-                         // matrix work overlaps the other's softmax arithmetic)
-constexpr int kSP = 4;   // pages (16 keys each) per ring stage: one barrier and one softmax update per 64 keys
-constexpr int kNS = 2;   // ring stages
+constexpr int kNW = 4;    // waves per block; two blocks share a compute unit
+constexpr int kDist = 1;  // rounds between a stage's loads and its use
 
 __device__ inline void dma16(unsigned lds_addr, unsigned lane_off, const void* base)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
+}
+
+__device__ inline void dma4(unsigned lds_addr, unsigned lane_off, const void* base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
                  :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
 }
 
@@ -59,16 +67,6 @@ __device__ inline void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
-// Wait until only the loads of `ahead` younger stages (N instructions of this wave each) are in flight.
-template <int N>
-__device__ inline void wait_stages(int ahead)
-{
-    static_assert(kNS <= 4, "one case per possible number of younger stages");
-    if (ahead >= 2) { wait_vmcnt<2 * N>(); return; }
-    if (ahead == 1) { wait_vmcnt<N>(); return; }
-    wait_vmcnt<0>();
-}
-
 __device__ inline const char* scalar_ptr(const char* ptr)
 {
     const uint64_t v = reinterpret_cast<uint64_t>(ptr);
@@ -86,23 +84,47 @@ struct PrefillArgs {
     int32_t nqb;              // query blocks per (request, kv head)
 };
 
+template <bool B>
+struct Flag { static constexpr bool value = B; };
+
+#ifdef JD_TIMING
+// Development aid (not built by default): shader-clock stamps of the first rounds of one block.
+constexpr int kStampRounds = 96, kStampPoints = 6;
+__device__ unsigned g_pstamps[8][kStampRounds][kStampPoints];
+#define JD_PSTAMP(i) do { if (stamping && stamp_round < kStampRounds && lane == 0) \
+        lstamps[w][stamp_round][(i)] = static_cast<unsigned>(__builtin_amdgcn_s_memtime()); } while (0)
+#else
+#define JD_PSTAMP(i) do { } while (0)
+#endif
+
 template <int D, int NT>
 __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillArgs a)
 {
+    constexpr int kSP = 4;   // pages (16 keys each) per ring stage: one barrier and one softmax update per 64 keys
     constexpr int kRowBytes = D * 2;
     constexpr int kPageBytes = kPage * kRowBytes;
-    constexpr int kPartsPerPage = 2 * kPageBytes / 1024;      // 1 KiB direct loads per page: 8 (D=128) or 4 (D=64)
-    constexpr int kSlotBytes = 2 * kPageBytes;                // K then V of one page
-    constexpr int kStageBytes = kSP * kSlotBytes;
-    constexpr int kHalfParts = kPartsPerPage / 2;             // parts of one tensor's page
-    constexpr int kLoadsPerWave = kSP * kPartsPerPage / kNW;  // direct loads a wave issues per stage (a K and a V part each time)
-    constexpr int kPageStride = kNW / kHalfParts;             // pages between two part pairs of a wave
-    static_assert(kNW % kHalfParts == 0 && kLoadsPerWave >= 2 && kLoadsPerWave % 2 == 0, "a wave keeps one part index");
+    constexpr int kStageBytes = kSP * kPageBytes;             // one tensor's share of a stage
+    constexpr int kHalfParts = kPageBytes / 1024;             // 1 KiB direct loads per page and tensor: 4 (D=128) or 2 (D=64)
+    constexpr int kLoadsPerWave = kSP * kHalfParts / kNW;     // direct loads a wave issues per stage and tensor
+    constexpr int kPageStride = kNW / kHalfParts;             // pages between two parts of a wave
+    static_assert(kNW % kHalfParts == 0 && kLoadsPerWave >= 1, "a wave keeps one part index");
     constexpr int CPR = kRowBytes / 16, RPL = 1024 / kRowBytes;
     constexpr int kRowShift = D == 128 ? 8 : 7;
     constexpr float kNegInf = -__builtin_inff();
-    static_assert(kLoadsPerWave * (kNS - 1) <= 63, "vmcnt is a 6-bit counter");
-    __shared__ __attribute__((aligned(1024))) char ring[kNS * kStageBytes];
+    // K and V rings of kDist + 1 stages: the loads of a stage are issued kDist rounds before its round
+    constexpr int kSlots = kDist + 1;
+    constexpr int kInFlight = (kDist - 1) * 2 * kLoadsPerWave;   // a wave's loads of the last kDist - 1 rounds
+    static_assert(kDist * 2 * kLoadsPerWave <= 63, "vmcnt is a 6-bit counter");
+    __shared__ __attribute__((aligned(1024))) char kring[kSlots * kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char vring[kSlots * kStageBytes];
+    // page ids of the request, two windows of 64 pages: page q sits at idring[q % 128]
+    __shared__ __attribute__((aligned(256))) int32_t idring[128];
+    constexpr int kWin = 64 / kSP;   // stages per window
+#ifdef JD_TIMING
+    __shared__ unsigned lstamps[8][kStampRounds][kStampPoints];
+    const bool stamping = blockIdx.x == gridDim.x / 2;
+    int stamp_round = 0;
+#endif
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -120,10 +142,9 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
     const int t0 = qb * tw * kNW;
     if (t0 >= n) return;
     const int qoff = uniform_load(a.q_offsets + b);
-    const int tw0 = t0 + w * tw;                          // first token of this wave
+    const int tw0 = min(t0 + w * tw, n - 1);              // first token of this wave (a wave past the end repeats the last token)
+    const bool wave_live = t0 + w * tw < n;
     const int blk_last = c + min(n, t0 + tw * kNW) - 1;   // last position any row of the block attends to
-    const int wave_last = c + min(n, tw0 + tw) - 1;       // same for this wave
-    const bool wave_live = tw0 < n;
     const int pend = blk_last / kPage + 1;                // pages the block sweeps (<= npages)
     const int nsteps = (pend + kSP - 1) / kSP;            // stages of kSP pages
 
@@ -136,8 +157,7 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
         const int row = 4 * kg + t16 / 4, cc = lane % 4;
         const int vs = D == 128 ? ((row & 7) << 1) : (((row >> 1) & 3) << 1);
 #pragma unroll
-        for (int jd = 0; jd < D / 16; ++jd)
-            v_rd[jd] = kPageBytes + row * kRowBytes + (((2 * jd + cc / 2) ^ vs) * 16) + (cc % 2) * 8;
+        for (int jd = 0; jd < D / 16; ++jd) v_rd[jd] = row * kRowBytes + (((2 * jd + cc / 2) ^ vs) * 16) + (cc % 2) * 8;
     }
     // this wave's share of a stage: the same 1 KiB part of K and of V of every kPageStride-th page,
     // starting at page w / kHalfParts
@@ -149,25 +169,47 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
         src_k = t * kRowBytes + ((cp ^ (t & (CPR - 1))) * 16);
         src_v = t * kRowBytes + ((cp ^ (D == 128 ? ((t & 7) << 1) : (((t >> 1) & 3) << 1))) * 16);
     }
-    const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<uintptr_t>((lds_char*)ring));
+    const unsigned k_base = static_cast<unsigned>(reinterpret_cast<uintptr_t>((lds_char*)kring));
+    const unsigned v_base = static_cast<unsigned>(reinterpret_cast<uintptr_t>((lds_char*)vring));
     const char* kpool = reinterpret_cast<const char*>(p.k_pages);
     const char* vpool = reinterpret_cast<const char*>(p.v_pages);
     const int32_t* bt = p.block_table + static_cast<size_t>(b) * p.maxp;
 
-    // Every wave issues the same number of loads for every stage: slots past the block's last page
-    // get that last page again (never read uninitialised memory, never count loads per wave).
-    auto issue = [&](int st) {
-#pragma unroll
-        for (int i = 0; i < kLoadsPerWave / 2; ++i) {
-            const int j = first_page + kPageStride * i;
-            const int pg = min(st * kSP + j, pend - 1);
-            const int id = checked_page(p, uniform_load(bt + pg));
-            const uint64_t off = static_cast<uint64_t>(static_cast<unsigned>(id * p.Hkv + kv)) << (kRowShift + 4);
-            const unsigned dst = lds_base + (st % kNS) * kStageBytes + j * kSlotBytes + part_j * 1024;
-            dma16(dst, src_k, scalar_ptr(kpool + off));
-            dma16(dst + kPageBytes, src_v, scalar_ptr(vpool + off));
-        }
+    // Every wave issues the same loads for every stage: slots past the block's last page get that
+    // last page again (no uninitialised memory is ever multiplied).  The block table reaches LDS through
+    // the same direct loads, a window of 64 page ids at a time and long before they are needed, so
+    // that no round waits for a table read; wave 0 refills the window everybody has left.
+    const unsigned id_base = static_cast<unsigned>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char*)idring));
+    auto fill_ids = [&](int win) __attribute__((always_inline)) {
+        if (w != 0) return;
+        const int pg = min(win * 64 + lane, pend - 1);
+        dma4(id_base + (win % 2) * 256, static_cast<unsigned>(pg) * 4u, bt);
     };
+    auto load_ids = [&](int st, int (&ids)[kLoadsPerWave]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < kLoadsPerWave; ++i)
+            ids[i] = __builtin_amdgcn_readfirstlane(idring[(st * kSP + first_page + kPageStride * i) & 127]);
+    };
+    bool bad_seen = false;
+    auto issue = [&](auto always, int st, int (&ids)[kLoadsPerWave]) __attribute__((always_inline)) {
+        if (!decltype(always)::value && st >= nsteps) return;
+        bool bad = false;
+#pragma unroll
+        for (int i = 0; i < kLoadsPerWave; ++i) {
+            const int j = first_page + kPageStride * i;
+            const bool ok = static_cast<unsigned>(ids[i]) < static_cast<unsigned>(p.NP);
+            bad |= !ok;
+            // a page id out of range reads page 0 and raises the sticky flag
+            const unsigned id = __builtin_amdgcn_readfirstlane(ok ? static_cast<unsigned>(ids[i]) : 0u);
+            const unsigned row = id * static_cast<unsigned>(p.Hkv) + static_cast<unsigned>(kv);
+            const uint64_t off = static_cast<uint64_t>(row) << (kRowShift + 4);
+            const unsigned dst = __builtin_amdgcn_readfirstlane((st % kSlots) * kStageBytes + j * kPageBytes + part_j * 1024);
+            dma16(k_base + dst, src_k, scalar_ptr(kpool + off));
+            dma16(v_base + dst, src_v, scalar_ptr(vpool + off));
+        }
+        bad_seen |= bad;
+    };
+    int ids[kLoadsPerWave];   // page ids of the next stage to issue
 
     // ---- queries of this wave: NT tiles of 16 rows, row = (token, head of the group) ----
     bf16x8 qreg[NT][D / 32];
@@ -176,7 +218,7 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const int tok = tw0 + nt * tpt + t16 / a.gp, g = t16 % a.gp;
-        row_ok[nt] = tok < n && g < p.G;
+        row_ok[nt] = wave_live && tok < n && g < p.G;
         const int tk = min(tok, n - 1), gg = min(g, p.G - 1);   // padding rows repeat a real row
         row_pos[nt] = c + tk;
         const uint16_t* src = a.q + (static_cast<size_t>(qoff + tk) * p.Hq + kv * p.G + gg) * D;
@@ -186,74 +228,70 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
     }
     f32x4 acc[NT][D / 16];
     f32x4 lacc[NT];       // softmax denominators (every register of a lane holds its row's)
-    float m[NT];
+    float m[NT], alpha[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         m[nt] = kNegInf;
+        alpha[nt] = 1.f;
         lacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int jd = 0; jd < D / 16; ++jd) acc[nt][jd] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the query loads are in before the page ring starts
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the query loads are in before the page rings start
 
-    // ---- sweep the stages ----
-    for (int s = 0; s < kNS - 1 && s < nsteps; ++s) issue(s);
-    for (int st = 0; st < nsteps; ++st) {
-        wait_stages<kLoadsPerWave>(min(kNS - 2, nsteps - 1 - st));
-        __syncthreads();   // every part of stage st has landed; everybody is done with stage st - 1
-        if (st + kNS - 1 < nsteps) issue(st + kNS - 1);
-        const int key0 = st * kSP * kPage;
-        if (!wave_live || key0 > wave_last) continue;
+    f32x4 sc[NT][kSP];                       // raw scores of the stage whose softmax comes next
+    u32x4 ph[NT][kSP / 2], pl[NT][kSP / 2];  // probabilities of the stage whose PV product comes next
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
 
-        const unsigned stage = lds_base + (st % kNS) * kStageBytes;
-        // S^T of every tile against the stage's keys (raw dot products; the scale is applied inside the exponent)
-        f32x4 sc[NT][kSP];
-        {
-            unsigned ka[D / 32];
+    // S^T = K Q^T of stage st for every tile (raw dot products; the scale is applied inside the exponent)
+    auto qk = [&](int st) __attribute__((always_inline)) {
+        unsigned ka[D / 32];
 #pragma unroll
-            for (int i = 0; i < D / 32; ++i) {
-                ka[i] = stage + k_rd[i];
-                asm volatile("" : "+v"(ka[i]));   // one add per stage; the page offset rides in the instruction
-            }
+        for (int i = 0; i < D / 32; ++i) {
+            ka[i] = k_base + (st % kSlots) * kStageBytes + k_rd[i];
+            asm volatile("" : "+v"(ka[i]));   // one add per stage; the page offset rides in the instruction
+        }
 #pragma unroll
-            for (int j = 0; j < kSP; ++j) {
-                bf16x8 kf[D / 32];
+        for (int j = 0; j < kSP; ++j) {
+            bf16x8 kf[D / 32];
 #pragma unroll
-                for (int i = 0; i < D / 32; ++i) kf[i] = *lds_ptr<bf16x8>(ka[i] + j * kSlotBytes);
+            for (int i = 0; i < D / 32; ++i) kf[i] = *lds_ptr<bf16x8>(ka[i] + j * kPageBytes);
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+            for (int nt = 0; nt < NT; ++nt) {
+                f32x4 s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int i = 0; i < D / 32; ++i)
-                        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[i], qreg[nt][i], s, 0, 0, 0);
-                    sc[nt][j] = s;
-                }
+                for (int i = 0; i < D / 32; ++i)
+                    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[i], qreg[nt][i], s, 0, 0, 0);
+                sc[nt][j] = s;
             }
         }
-        // keys after a row's own position (and the slots past the sequence's end) are excluded by selection
-        if (key0 + kSP * kPage - 1 > c + tw0) {
+    };
+
+    // Online softmax of stage st: sc -> ph, pl (bf16 head + bf16 remainder, two pages side by side: the
+    // 8 keys a lane holds of a page pair are one k-group of a 32-deep contraction), m, alpha.  With
+    // `masked`, keys after a row's own position (and slots past the sequence's end) are excluded by selection.
+    auto softmax = [&](auto masked, int st) __attribute__((always_inline)) {
+        const int key0 = st * kSP * kPage;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
+        for (int nt = 0; nt < NT; ++nt) {
+            if (decltype(masked)::value) {
 #pragma unroll
                 for (int j = 0; j < kSP; ++j)
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
                         if (key0 + j * kPage + 4 * kg + r > row_pos[nt]) sc[nt][j][r] = kNegInf;
-        }
-        // online softmax per tile (the scale is positive, so the maximum can be taken before scaling);
-        // probabilities as bf16 head + bf16 remainder, two pages side by side: the 8 keys a lane holds
-        // of a page pair are one k-group of a 32-deep contraction
-        u32x4 ph[NT][kSP / 2], pl[NT][kSP / 2];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
+            }
             float mx = max3(sc[nt][0][0], sc[nt][0][1], sc[nt][0][2]);
 #pragma unroll
             for (int e = 3; e < 4 * kSP; e += 2)   // two more values per instruction; the odd one out pairs with itself
                 mx = max3(mx, sc[nt][e / 4][e % 4], e + 1 < 4 * kSP ? sc[nt][(e + 1) / 4][(e + 1) % 4] : mx);
             mx = max3(mx, __shfl_xor(mx, 16, 64), mx);
             mx = max3(mx, __shfl_xor(mx, 32, 64), mx);
-            const float mn = max3(m[nt], mx * p.scale_log2e, m[nt]);   // finite from the first stage on: position 0 is visible to every row
-            const float alpha = __builtin_amdgcn_exp2f(m[nt] - mn);
+            // the scale is positive, so the maximum can be taken before scaling; mn is finite from the
+            // first stage on, because position 0 is visible to every row
+            const float mn = max3(m[nt], mx * p.scale_log2e, m[nt]);
+            alpha[nt] = __builtin_amdgcn_exp2f(m[nt] - mn);
+            m[nt] = mn;
 #pragma unroll
             for (int j = 0; j < kSP; ++j)
 #pragma unroll
@@ -266,24 +304,21 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
                     ph[nt][j / 2][2 * (j % 2) + r / 2] = __builtin_bit_cast(uint32_t, hi);
                     pl[nt][j / 2][2 * (j % 2) + r / 2] = __builtin_bit_cast(uint32_t, lo);
                 }
-            if (__builtin_amdgcn_ballot_w64(mn > m[nt]) != 0) {   // nobody's maximum moved: alpha is exactly 1 everywhere
-                lacc[nt] *= alpha;
-#pragma unroll
-                for (int jd = 0; jd < D / 16; ++jd) acc[nt][jd] *= alpha;
-            }
-            m[nt] = mn;
         }
-        // O^T += V^T P^T, 32 keys per instruction; the row sums of P come from the same unit (V^T replaced by ones)
-        unsigned va_[D / 16];
+    };
+
+    // O^T += V^T P^T of stage st, 32 keys per instruction; the row sums of P come from the same unit
+    // (V^T replaced by ones).  With `ragged`, value rows past the sequence's end are zeroed first.
+    auto pv = [&](auto ragged, int st) __attribute__((always_inline)) {
+        const int key0 = st * kSP * kPage;
+        unsigned va[D / 16];
 #pragma unroll
         for (int jd = 0; jd < D / 16; ++jd) {
-            va_[jd] = stage + v_rd[jd];
-            asm volatile("" : "+v"(va_[jd]));
+            va[jd] = v_base + (st % kSlots) * kStageBytes + v_rd[jd];
+            asm volatile("" : "+v"(va[jd]));
         }
-        const bf16x8 ones = __builtin_bit_cast(bf16x8, u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
 #pragma unroll
         for (int jp = 0; jp < kSP / 2; ++jp) {
-            const bool ragged = L - (key0 + (2 * jp + 1) * kPage) < kPage;   // the pair reaches past the sequence's end
             bf16x8 bh[NT], bl[NT];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
@@ -291,6 +326,15 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
                 bl[nt] = __builtin_bit_cast(bf16x8, pl[nt][jp]);
                 lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bh[nt], lacc[nt], 0, 0, 0);
                 lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bl[nt], lacc[nt], 0, 0, 0);
+            }
+            uint32_t keep[2][2];
+            if (decltype(ragged)::value) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int valid = L - (key0 + (2 * jp + h) * kPage);   // tokens of this page that exist (<= 0: a repeated page)
+                    keep[h][0] = (4 * kg + 0 < valid ? 0x0000ffffu : 0u) | (4 * kg + 1 < valid ? 0xffff0000u : 0u);
+                    keep[h][1] = (4 * kg + 2 < valid ? 0x0000ffffu : 0u) | (4 * kg + 3 < valid ? 0xffff0000u : 0u);
+                }
             }
 #pragma unroll
             for (int q4 = 0; q4 < D / 64; ++q4) {   // four 16-wide slices of the head dimension at a time
@@ -300,18 +344,11 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const u32x2 t = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            lds_ptr<s16x4>(va_[4 * q4 + e] + (2 * jp + h) * kSlotBytes)));
+                            lds_ptr<s16x4>(va[4 * q4 + e] + (2 * jp + h) * kPageBytes)));
                         vf[e][2 * h] = t[0];
                         vf[e][2 * h + 1] = t[1];
                     }
-                if (ragged) {
-                    uint32_t keep[2][2];
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const int valid = L - (key0 + (2 * jp + h) * kPage);   // tokens of this page that exist (<= 0: a repeated page)
-                        keep[h][0] = (4 * kg + 0 < valid ? 0x0000ffffu : 0u) | (4 * kg + 1 < valid ? 0xffff0000u : 0u);
-                        keep[h][1] = (4 * kg + 2 < valid ? 0x0000ffffu : 0u) | (4 * kg + 3 < valid ? 0xffff0000u : 0u);
-                    }
+                if (decltype(ragged)::value) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         vf[e][0] &= keep[0][0]; vf[e][1] &= keep[0][1];
@@ -322,16 +359,80 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
                 for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const bf16x8 va = __builtin_bit_cast(bf16x8, vf[e]);
-                        acc[nt][4 * q4 + e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, bh[nt], acc[nt][4 * q4 + e], 0, 0, 0);
-                        acc[nt][4 * q4 + e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, bl[nt], acc[nt][4 * q4 + e], 0, 0, 0);
+                        const bf16x8 vt = __builtin_bit_cast(bf16x8, vf[e]);
+                        acc[nt][4 * q4 + e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, bh[nt], acc[nt][4 * q4 + e], 0, 0, 0);
+                        acc[nt][4 * q4 + e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, bl[nt], acc[nt][4 * q4 + e], 0, 0, 0);
                     }
             }
         }
-    }
+    };
 
+    // alpha of the last softmax is applied once the PV product issued before it is through
+    auto rescale = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            if (__builtin_amdgcn_ballot_w64(alpha[nt] != 1.f) != 0) {   // nobody's maximum moved: alpha is exactly 1 everywhere
+                lacc[nt] *= alpha[nt];
+#pragma unroll
+                for (int jd = 0; jd < D / 16; ++jd) acc[nt][jd] *= alpha[nt];
+            }
+        }
+    };
+
+    // One round: the scores of stage st, its softmax, its PV product.  The loads of stage st + kDist go
+    // out among the matrix instructions of the scores.
+    auto round = [&](auto steady, auto masked, auto ragged, int st) __attribute__((always_inline)) {
+        JD_PSTAMP(0);
+        if (decltype(steady)::value || st + kDist - 1 < nsteps) wait_vmcnt<kInFlight>(); else wait_vmcnt<0>();
+        JD_PSTAMP(1);
+        __syncthreads();   // stage st has landed; everybody is through round st - 1
+        JD_PSTAMP(2);
+        // every id of window (st + kDist) / kWin - 1 has been read by now: its slot takes the window after next
+        if ((st + kDist) % kWin == 0) fill_ids((st + kDist) / kWin + 1);
+        qk(st);
+        issue(steady, st + kDist, ids);
+        load_ids(st + kDist + 1, ids);
+        JD_PSTAMP(3);
+        softmax(masked, st);
+        rescale();
+        JD_PSTAMP(4);
+        pv(ragged, st);
+        JD_PSTAMP(5);
+#ifdef JD_TIMING
+        ++stamp_round;
+#endif
+    };
+
+    // ---- prologue: the first kDist stages ----
+    fill_ids(0);
+    fill_ids(1);
+    wait_vmcnt<0>();
+    __syncthreads();
+#pragma unroll
+    for (int x = 0; x < kDist; ++x) {
+        load_ids(x, ids);
+        issue(Flag<false>{}, x, ids);
+    }
+    load_ids(kDist, ids);
+
+    // ---- rounds ----
+    // the softmax of stage st needs the mask once the stage reaches past the wave's first row
+    const int first_masked = (c + tw0 >= kSP * kPage - 1) ? (c + tw0 - (kSP * kPage - 1)) / (kSP * kPage) + 1 : 0;
+    int st = 0;
+    // steady rounds: the stage they issue exists, no softmax needs the mask, no value row lies past the end
+    for (; st + kDist < nsteps && st < first_masked; ++st) round(Flag<true>{}, Flag<false>{}, Flag<false>{}, st);
+    for (; st < nsteps - 1; ++st) round(Flag<false>{}, Flag<true>{}, Flag<false>{}, st);
+    round(Flag<false>{}, Flag<true>{}, Flag<true>{}, nsteps - 1);
+    if (bad_seen && lane == 0) atomicOr(&p.header[kHdrBadInput], 2);
+
+#ifdef JD_TIMING
+    if (stamping) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < 8 * kStampRounds * kStampPoints; i += kNW * 64)
+            (&g_pstamps[0][0][0])[i] = (&lstamps[0][0][0])[i];
+    }
+#endif
     // ---- normalise and store ----
-    if (!wave_live) return;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const float lt = lacc[nt][0];
@@ -353,9 +454,16 @@ int prefill_block_tokens(int G, int D)
 {
     int gp = 1;
     while (gp < G) gp *= 2;
-    const int nt = D == 128 ? 2 : 4;
+    const int nt = 2;
     return kNW * nt * (16 / gp);
 }
+
+#ifdef JD_TIMING
+extern "C" int jd_debug_read_pstamps(unsigned* host)
+{
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_pstamps), sizeof(unsigned) * 8 * kStampRounds * kStampPoints) == hipSuccess ? 0 : 1;
+}
+#endif
 
 hipError_t launch_prefill(const Params& p, const uint16_t* q, const int32_t* q_lens, const int32_t* q_offsets,
                           int max_q_len, float* out, hipStream_t stream)
@@ -372,7 +480,7 @@ hipError_t launch_prefill(const Params& p, const uint16_t* q, const int32_t* q_l
     if (p.D == 128)
         hipLaunchKernelGGL((prefill_kernel<128, 2>), grid, dim3(kNW * 64), 0, stream, p, a);
     else
-        hipLaunchKernelGGL((prefill_kernel<64, 4>), grid, dim3(kNW * 64), 0, stream, p, a);
+        hipLaunchKernelGGL((prefill_kernel<64, 2>), grid, dim3(kNW * 64), 0, stream, p, a);
     return hipGetLastError();
 }
 

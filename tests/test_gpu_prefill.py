@@ -114,3 +114,36 @@ def test_no_new_tokens_writes_nothing(torch_cuda, jo):
     assert np.all(got == 777.0)
     got = run_prefill(torch_cuda, w, q, ql, offs, max_q_len=64)
     assert np.all(got == 777.0)
+
+
+def test_bad_page_id_is_flagged_not_dereferenced(torch_cuda):
+    from paper_2604_23838_amd import binding as jb
+    w = W.gen_config(1, 0)
+    bt = w.block_table.copy()
+    bt[3, 40] = w.num_pages + 12345       # a page in the middle of the longest request
+    bt[1, 0] = -7
+    bad = W.Workload(w.cfg, w.seed, w.shape, w.q, w.k_pages, w.v_pages, bt, w.seq_lens)
+    ql = np.array([5, 100, 0, 64], dtype=np.int32)
+    q, ql, offs = prefill_inputs(bad, ql, seed=3)
+    with pytest.raises(jb.JdError) as e:
+        run_prefill(torch_cuda, bad, q, ql, offs)
+    assert e.value.status == jb.JD_ERR_BAD_INPUT
+
+
+def test_random_shapes_and_chunks(torch_cuda, jo):
+    # a seeded sweep over head layouts, both head sizes, contexts and chunk lengths
+    rng = np.random.default_rng(77)
+    heads = [(1, 1), (3, 1), (5, 5), (6, 2), (8, 8), (12, 4), (16, 2), (16, 1), (24, 8), (40, 8)]
+    for case in range(16):
+        hq, hkv = heads[rng.integers(len(heads))]
+        d = int(rng.choice([64, 128]))
+        B = int(rng.integers(1, 12))
+        lens = np.floor(rng.lognormal(np.log(200.0), 1.2, size=B)).clip(0, 3000).astype(np.int32)
+        frac = rng.random(B)
+        ql = np.where(rng.random(B) < 0.25, lens, np.floor(lens * frac)).astype(np.int32)   # whole prompts and chunks
+        ql = np.minimum(ql, 700)
+        w = W.build(W.Shape("t", 0, hq, hkv, d, 1), lens, seed=100 + case, cfg=85)
+        q, ql, offs = prefill_inputs(w, ql, seed=200 + case)
+        ref = jo.prefill_attention(q, w.k_pages, w.v_pages, w.block_table, w.seq_lens, ql, offs)
+        got = run_prefill(torch_cuda, w, q, ql, offs, max_q_len=int(max(int(ql.max()), 1)))
+        check(got, ref, ql, offs)
