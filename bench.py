@@ -35,10 +35,11 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--variant", type=int, default=0, help="0 default, 1 vector, 2 mfma")
     ap.add_argument("--cu-budget", type=int, default=0)
-    ap.add_argument("--sweep", choices=["none", "cu", "batch", "loop", "prefill"], default="none",
+    ap.add_argument("--sweep", choices=["none", "cu", "batch", "merge", "loop", "prefill"], default="none",
                     help="extra measurements after the timed region: 'cu' = step time at 25/50/75/100 %% of the "
                          "compute units (the library's cu_budget), 'batch' = step time as the batch shrinks to its "
-                         "longest requests, 'loop' = the closed decode loop (KV append + attention) eager and as a replayed "
+                         "longest requests, 'merge' = the straggler batches of n = 1, 2, 4, 8 workers (cfg3 draws) merged into one, "
+                         "'loop' = the closed decode loop (KV append + attention) eager and as a replayed "
                          "HIP graph, 'prefill' = causal prefill over the paged cache (KV recomputation of migrated requests, "
                          "a new turn after a context) against the matrix-core peak")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -199,6 +200,40 @@ def main() -> int:
         with torch.cuda.stream(stream):
             op(q, kp, vp, bt, sl, out)     # restore the full batch's output for the parity check below
             torch.cuda.synchronize()
+
+    if args.sweep == "merge":
+        # long-tail migration aggregates the stragglers of n DP workers on one target (Sub-stage Merging):
+        # n independent cfg3 draws merged into one batch; a bandwidth-bound kernel should charge the sum of the bytes
+        s3 = W.SHAPES[3]
+        rows = []
+        for n in (1, 2, 4, 8):
+            lens_m = np.concatenate([W.draw_seq_lens(3, np.random.default_rng(args.seed + i)) for i in range(n)])
+            wm = W.build(dataclasses.replace(s3, batch=len(lens_m)), lens_m, seed=args.seed, cfg=30 + n,
+                         threads=min(16, os.cpu_count() or 8))
+            qm = torch.from_numpy(wm.q.view(np.int16)).to(dev).view(torch.bfloat16)
+            km = torch.from_numpy(wm.k_pages.view(np.int16)).to(dev).view(torch.bfloat16)
+            vm = torch.from_numpy(wm.v_pages.view(np.int16)).to(dev).view(torch.bfloat16)
+            btm = torch.from_numpy(wm.block_table).to(dev)
+            slm = torch.from_numpy(wm.seq_lens).to(dev)
+            om = torch.empty((len(lens_m), s3.num_q_heads, s3.head_dim), dtype=torch.float32, device=dev)
+            o2 = jb.DecodeAttention(len(lens_m), s3.num_q_heads, s3.num_kv_heads, s3.head_dim, wm.max_pages_per_seq,
+                                    wm.num_pages, variant=args.variant)
+            with torch.cuda.stream(stream):
+                for _ in range(10):
+                    o2(qm, km, vm, btm, slm, om)
+                torch.cuda.synchronize()
+                t0_ = time.perf_counter()
+                for _ in range(100):
+                    o2(qm, km, vm, btm, slm, om)
+                torch.cuda.synchronize()
+                us = (time.perf_counter() - t0_) * 1e6 / 100
+            o2.close()
+            rows.append({"workers_merged": n, "requests": len(lens_m), "tokens": wm.total_tokens,
+                         "us_per_step": round(us, 2), "kv_tb_per_s": round(wm.kv_bytes / us / 1e6, 4)})
+            del qm, km, vm, om
+        for r in rows:
+            r["us_vs_n_times_single"] = round(r["us_per_step"] / (rows[0]["us_per_step"] * r["workers_merged"]), 3)
+        result["merged_straggler_sweep"] = rows
 
     if args.sweep == "loop":
         # a closed decode loop: every step appends one token per request and attends over the grown cache.
