@@ -238,6 +238,12 @@ jd_status jd_prefill_attention(jd_handle* h, const void* q, const void* k_pages,
         return fail(h, JD_ERR_INVALID_ARG, "q, k_pages, v_pages and out must be 16-byte aligned");
     if (max_q_len < 0) return fail(h, JD_ERR_INVALID_ARG, "max_q_len must be >= 0");
     jd::Params p = h->params;
+    // a request never has more new tokens than its table holds; the launch is sized for the bound
+    const int64_t cap = static_cast<int64_t>(p.maxp) * jd::kPage;
+    if (max_q_len > cap) max_q_len = static_cast<int32_t>(cap);
+    const int64_t blocks = (static_cast<int64_t>(max_q_len) + jd::prefill_block_tokens(p.G, p.D) - 1) /
+                           jd::prefill_block_tokens(p.G, p.D) * p.B * p.Hkv;
+    if (blocks > 0x7fffffff) return fail(h, JD_ERR_UNSUPPORTED, "batch x kv heads x query blocks exceeds the launch limit");
     p.k_pages = static_cast<const uint16_t*>(k_pages);
     p.v_pages = static_cast<const uint16_t*>(v_pages);
     p.block_table = block_table;

@@ -60,6 +60,8 @@ def test_config_validation_without_gpu():
 def test_null_handle_and_pointer_errors_without_gpu():
     lib = jb.lib()
     assert lib.jd_decode_attention(None, 1, 1, 1, 1, 1, 1, None) == jb.JD_ERR_INVALID_ARG
+    assert lib.jd_prefill_attention(None, 1, 1, 1, 1, 1, 1, 1, 16, 1, None) == jb.JD_ERR_INVALID_ARG
+    assert lib.jd_append_kv(None, 1, 1, 1, 1, 1, 1, None, None) == jb.JD_ERR_INVALID_ARG
     assert lib.jd_check_device_flags(None, None) == jb.JD_ERR_INVALID_ARG
     assert lib.jd_debug_partition(None, None, None, None, None, None) == jb.JD_ERR_INVALID_ARG
     assert lib.jd_profile_enable(None, 1, 1) == jb.JD_ERR_INVALID_ARG
