@@ -119,3 +119,36 @@ def test_generator_matches_documented_totals():
     w = W.gen_config(1, 0)
     assert w.total_tokens == 1367 and w.kv_bytes == 1367 * 2 * 2 * 64 * 2
     assert w.block_table.min() == -1 and len(set(w.block_table[w.block_table >= 0].tolist())) == (w.block_table >= 0).sum()
+
+
+def test_header_compiles_as_c99_and_links_from_plain_c(tmp_path):
+    # the boundary is a C ABI: a C99 translation unit includes the header, links the library and calls it
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    libdir = os.path.join(root, "paper_2604_23838_amd")
+    if not os.path.exists(os.path.join(libdir, "libjigsaw_decode.so")):
+        pytest.skip("library not built")
+    src = tmp_path / "use.c"
+    src.write_text(r'''
+#include "jigsaw_decode.h"
+#include <stdio.h>
+int main(void) {
+    jd_config c = {0};
+    c.batch = 4; c.num_q_heads = 8; c.num_kv_heads = 2; c.head_dim = 64; c.page_size = 16;
+    c.max_pages_per_seq = 8; c.num_pages = 64;
+    if (jd_validate_config(&c) != JD_OK || jd_workspace_bytes(&c) <= 0) return 1;
+    c.head_dim = 96;
+    if (jd_validate_config(&c) != JD_ERR_UNSUPPORTED) return 2;
+    if (jd_decode_attention(0, 0, 0, 0, 0, 0, 0, 0) != JD_ERR_INVALID_ARG) return 3;
+    if (jd_prefill_attention(0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0) != JD_ERR_INVALID_ARG) return 4;
+    puts(jd_last_error_string(0));
+    return 0;
+}
+''')
+    exe = tmp_path / "use"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+                           str(src), "-o", str(exe), "-L", libdir, "-ljigsaw_decode", f"-Wl,-rpath,{libdir}"])
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0, out.stdout + out.stderr
+    assert "NULL" in out.stdout
