@@ -15,7 +15,8 @@
 //   l[row]        += 1 . P^T   (row sums from the matrix unit, V^T replaced by ones),
 // with V read transposed from LDS.  Keys after a row's own position are excluded by selection (only
 // in the rounds that reach the diagonal); pages wholly above the block's last position are never
-// fetched.  Query blocks of a request are launched heaviest first.
+// fetched.  Requests are dispatched by decreasing work (a small ranking kernel runs first), the query
+// blocks of a request heaviest first.
 #include "jd_internal.h"
 #include "jd_walk.h"
 
@@ -82,7 +83,36 @@ struct PrefillArgs {
     float* out;               // fp32 [TQ, Hq, D]
     int32_t gp;               // group size padded to a power of two (query heads per token in a tile)
     int32_t nqb;              // query blocks per (request, kv head)
+    const int32_t* order;     // [B] requests by decreasing work
 };
+
+// Requests by decreasing work (query-key pairs under the causal mask), so that the blocks of the heaviest
+// request are dispatched first and the launch ends on light ones.  Rank by counting: ties go to the lower
+// index, so the ranks are a permutation whatever the lengths hold.
+__global__ __launch_bounds__(256) void prefill_order_kernel(Params p, const int32_t* q_lens, int32_t* order)
+{
+    __shared__ long long tile[256];
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    auto work = [&](int i) -> long long {
+        const int L0 = p.seq_lens[i];
+        const long long L = min(max(L0, 0), p.maxp * kPage);
+        const long long n = min(static_cast<long long>(max(q_lens[i], 0)), L);
+        return n * (2 * (L - n) + n + 1);
+    };
+    const long long mine = b < p.B ? work(b) : -1;
+    int rank = 0;
+    for (int base = 0; base < p.B; base += 256) {
+        __syncthreads();
+        tile[threadIdx.x] = base + threadIdx.x < p.B ? work(base + threadIdx.x) : -1;
+        __syncthreads();
+        const int m = min(256, p.B - base);
+        for (int i = 0; i < m; ++i) {
+            const long long o = tile[i];
+            rank += (o > mine || (o == mine && base + i < b)) ? 1 : 0;
+        }
+    }
+    if (b < p.B) order[rank] = b;
+}
 
 template <bool B>
 struct Flag { static constexpr bool value = B; };
@@ -129,7 +159,7 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int bkv = blockIdx.x / a.nqb;
-    const int b = bkv / p.Hkv, kv = bkv % p.Hkv;
+    const int b = uniform_load(a.order + bkv / p.Hkv), kv = bkv % p.Hkv;
     const int L0 = uniform_load(p.seq_lens + b);
     int n = uniform_load(a.q_lens + b);
     const int npages = min(L0 > 0 ? (L0 + kPage - 1) / kPage : 0, p.maxp);
@@ -476,6 +506,8 @@ hipError_t launch_prefill(const Params& p, const uint16_t* q, const int32_t* q_l
     a.nqb = (max_q_len + qb - 1) / qb;
     if (a.nqb == 0 || p.B == 0) return hipSuccess;
     if (static_cast<int64_t>(a.nqb) * p.B * p.Hkv > 0x7fffffff) return hipErrorInvalidValue;
+    a.order = p.req;   // workspace the decode call uses too: calls on a handle are stream-ordered
+    hipLaunchKernelGGL(prefill_order_kernel, dim3((p.B + 255) / 256), dim3(256), 0, stream, p, q_lens, p.req);
     const dim3 grid(static_cast<unsigned>(a.nqb * p.B * p.Hkv));
     if (p.D == 128)
         hipLaunchKernelGGL((prefill_kernel<128, 2>), grid, dim3(kNW * 64), 0, stream, p, a);
