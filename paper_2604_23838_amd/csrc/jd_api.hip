@@ -241,8 +241,8 @@ jd_status jd_prefill_attention(jd_handle* h, const void* q, const void* k_pages,
     // a request never has more new tokens than its table holds; the launch is sized for the bound
     const int64_t cap = static_cast<int64_t>(p.maxp) * jd::kPage;
     if (max_q_len > cap) max_q_len = static_cast<int32_t>(cap);
-    const int64_t blocks = (static_cast<int64_t>(max_q_len) + jd::prefill_block_tokens(p.G, p.D) - 1) /
-                           jd::prefill_block_tokens(p.G, p.D) * p.B * p.Hkv;
+    if (cap * p.G > 0x7fffffff) return fail(h, JD_ERR_UNSUPPORTED, "max_pages_per_seq x 16 x group size exceeds the row index range");
+    const int64_t blocks = static_cast<int64_t>(jd::prefill_query_blocks(max_q_len, p.G)) * p.B * p.Hkv;
     if (blocks > 0x7fffffff) return fail(h, JD_ERR_UNSUPPORTED, "batch x kv heads x query blocks exceeds the launch limit");
     p.k_pages = static_cast<const uint16_t*>(k_pages);
     p.v_pages = static_cast<const uint16_t*>(v_pages);

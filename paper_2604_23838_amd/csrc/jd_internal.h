@@ -64,7 +64,7 @@ hipError_t launch_append_kv(const Params& p, const uint16_t* k_new, const uint16
 
 hipError_t launch_prefill(const Params& p, const uint16_t* q, const int32_t* q_lens, const int32_t* q_offsets,
                           int max_q_len, float* out, hipStream_t stream);
-int prefill_block_tokens(int G, int D);
+int prefill_query_blocks(int max_q_len, int G);
 
 // Wave slots each variant wants per compute unit.
 int vector_waves_per_cu();

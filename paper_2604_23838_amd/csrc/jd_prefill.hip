@@ -4,8 +4,8 @@
 //
 // One block of kNW waves serves one (request, kv head, block of query tokens); two blocks share a
 // compute unit, so that one's matrix work runs while the other's softmax arithmetic does.  Each wave
-// holds NT tiles of 16 query rows in registers (a row is a (token, query head of the group) pair, the
-// group padded to a power of two), and all waves sweep the same K/V pages, which the block stages in
+// holds NT tiles of 16 query rows in registers (row r of a request's kv head is query head r % G of new
+// token r / G, packed densely whatever G is), and all waves sweep the same K/V pages, which the block stages in
 // shared LDS rings of 64-key stages with direct loads (each wave issues its share of a stage; one
 // barrier and one softmax update per stage).  The block table reaches LDS the same way, a window of
 // 64 page ids at a time, so no round waits for a table read.  Per stage and tile:
@@ -35,6 +35,7 @@ typedef __attribute__((address_space(3))) char lds_char;
 
 constexpr int kNW = 4;    // waves per block; two blocks share a compute unit
 constexpr int kDist = 1;  // rounds between a stage's loads and its use
+constexpr int kPrefillBlockRows = kNW * 2 * 16;   // query rows (token x head of the group) per block: 2 tiles of 16 per wave
 
 __device__ inline void dma16(unsigned lds_addr, unsigned lane_off, const void* base)
 {
@@ -81,7 +82,6 @@ struct PrefillArgs {
     const int32_t* q_lens;    // [B]
     const int32_t* q_offsets; // [B]
     float* out;               // fp32 [TQ, Hq, D]
-    int32_t gp;               // group size padded to a power of two (query heads per token in a tile)
     int32_t nqb;              // query blocks per (request, kv head)
     const int32_t* order;     // [B] requests by decreasing work
 };
@@ -159,22 +159,25 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int bkv = blockIdx.x / a.nqb;
-    const int b = uniform_load(a.order + bkv / p.Hkv), kv = bkv % p.Hkv;
+    const int b = min(max(uniform_load(a.order + bkv / p.Hkv), 0), p.B - 1), kv = bkv % p.Hkv;
     const int L0 = uniform_load(p.seq_lens + b);
     int n = uniform_load(a.q_lens + b);
     const int npages = min(L0 > 0 ? (L0 + kPage - 1) / kPage : 0, p.maxp);
     const int L = min(L0, npages * kPage);
     if (n > L) n = L;                      // malformed: more new tokens than the cache holds
     const int c = L - n;                   // tokens of context in front of the new ones
-    const int tpt = 16 / a.gp;             // tokens per tile
-    const int tw = NT * tpt;               // tokens per wave
+    // query rows of the request: row r is head r % G of new token r / G (no padding of the group)
+    constexpr int kWaveRows = NT * 16;
+    static_assert(kNW * kWaveRows == kPrefillBlockRows, "the launch and the kernel agree on the rows of a block");
+    const int nrows = n * p.G;
     const int qb = a.nqb - 1 - static_cast<int>(blockIdx.x % a.nqb);   // heaviest query block first
-    const int t0 = qb * tw * kNW;
-    if (t0 >= n) return;
+    const int r0 = qb * kPrefillBlockRows;
+    if (r0 >= nrows) return;
     const int qoff = uniform_load(a.q_offsets + b);
-    const int tw0 = min(t0 + w * tw, n - 1);              // first token of this wave (a wave past the end repeats the last token)
-    const bool wave_live = t0 + w * tw < n;
-    const int blk_last = c + min(n, t0 + tw * kNW) - 1;   // last position any row of the block attends to
+    const int rw0 = min(r0 + w * kWaveRows, nrows - 1);   // first row of this wave (a wave past the end repeats the last row)
+    const bool wave_live = r0 + w * kWaveRows < nrows;
+    const int tw0 = rw0 / p.G;                            // the token of that row
+    const int blk_last = c + (min(nrows, r0 + kPrefillBlockRows) - 1) / p.G;   // last position any row of the block attends to
     const int pend = blk_last / kPage + 1;                // pages the block sweeps (<= npages)
     const int nsteps = (pend + kSP - 1) / kSP;            // stages of kSP pages
 
@@ -247,9 +250,10 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
     bool row_ok[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int tok = tw0 + nt * tpt + t16 / a.gp, g = t16 % a.gp;
-        row_ok[nt] = wave_live && tok < n && g < p.G;
-        const int tk = min(tok, n - 1), gg = min(g, p.G - 1);   // padding rows repeat a real row
+        const int r = r0 + w * kWaveRows + nt * 16 + t16;
+        row_ok[nt] = wave_live && r < nrows;
+        const int rc = min(r, nrows - 1);   // rows past the end repeat the last real row
+        const int tk = rc / p.G, gg = rc % p.G;
         row_pos[nt] = c + tk;
         const uint16_t* src = a.q + (static_cast<size_t>(qoff + tk) * p.Hq + kv * p.G + gg) * D;
 #pragma unroll
@@ -418,7 +422,8 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
         __syncthreads();   // stage st has landed; everybody is through round st - 1
         JD_PSTAMP(2);
         // every id of window (st + kDist) / kWin - 1 has been read by now: its slot takes the window after next
-        if ((st + kDist) % kWin == 0) fill_ids((st + kDist) / kWin + 1);
+        // (a window no stage of which will be issued is not fetched: no load may be in flight when the block ends)
+        if ((st + kDist) % kWin == 0 && ((st + kDist) / kWin + 1) * kWin < nsteps) fill_ids((st + kDist) / kWin + 1);
         qk(st);
         issue(steady, st + kDist, ids);
         load_ids(st + kDist + 1, ids);
@@ -453,6 +458,7 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
     for (; st + kDist < nsteps && st < first_masked; ++st) round(Flag<true>{}, Flag<false>{}, Flag<false>{}, st);
     for (; st < nsteps - 1; ++st) round(Flag<false>{}, Flag<true>{}, Flag<false>{}, st);
     round(Flag<false>{}, Flag<true>{}, Flag<true>{}, nsteps - 1);
+    wait_vmcnt<0>();   // nothing of this wave's may still be on its way into LDS when the block retires
     if (bad_seen && lane == 0) atomicOr(&p.header[kHdrBadInput], 2);
 
 #ifdef JD_TIMING
@@ -467,7 +473,8 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
     for (int nt = 0; nt < NT; ++nt) {
         const float lt = lacc[nt][0];
         if (!row_ok[nt]) continue;
-        const int tok = tw0 + nt * tpt + t16 / a.gp, g = t16 % a.gp;
+        const int r = r0 + w * kWaveRows + nt * 16 + t16;
+        const int tok = r / p.G, g = r % p.G;
         const float inv = 1.f / lt;
         float* o = a.out + (static_cast<size_t>(qoff + tok) * p.Hq + kv * p.G + g) * D + 4 * kg;
 #pragma unroll
@@ -479,13 +486,10 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
 
 }  // namespace
 
-// Tokens of one request a block covers, for a group size G.
-int prefill_block_tokens(int G, int D)
+// Query blocks per (request, kv head) for requests of up to max_q_len new tokens.
+int prefill_query_blocks(int max_q_len, int G)
 {
-    int gp = 1;
-    while (gp < G) gp *= 2;
-    const int nt = 2;
-    return kNW * nt * (16 / gp);
+    return static_cast<int>((static_cast<int64_t>(max_q_len) * G + kPrefillBlockRows - 1) / kPrefillBlockRows);
 }
 
 #ifdef JD_TIMING
@@ -500,10 +504,7 @@ hipError_t launch_prefill(const Params& p, const uint16_t* q, const int32_t* q_l
 {
     PrefillArgs a;
     a.q = q; a.q_lens = q_lens; a.q_offsets = q_offsets; a.out = out;
-    a.gp = 1;
-    while (a.gp < p.G) a.gp *= 2;
-    const int qb = prefill_block_tokens(p.G, p.D);
-    a.nqb = (max_q_len + qb - 1) / qb;
+    a.nqb = prefill_query_blocks(max_q_len, p.G);
     if (a.nqb == 0 || p.B == 0) return hipSuccess;
     if (static_cast<int64_t>(a.nqb) * p.B * p.Hkv > 0x7fffffff) return hipErrorInvalidValue;
     a.order = p.req;   // workspace the decode call uses too: calls on a handle are stream-ordered
