@@ -55,12 +55,22 @@ __device__ inline __attribute__((address_space(3))) T* lds_ptr(unsigned addr)
     return (__attribute__((address_space(3))) T*)(uintptr_t)addr;
 }
 
-// max of three floats without the canonicalising moves fmaxf brings (inputs are never signalling NaNs here)
-__device__ inline float max3(float a, float b, float c)
+// Row maximum of the scores a lane group holds.  Plain compiler-visible maxima on purpose: the compiler
+// places the wait states that a read of a fresh matrix result needs, which it cannot do for an
+// instruction hidden in inline assembly (a hand-written v_max3 here once read scores before the matrix
+// unit had written them: right to rounding, since only the reference maximum moved, but not repeatable).
+template <int N>
+__device__ inline float row_max(const f32x4 (&s)[N])
 {
-    float d;
-    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
-    return d;
+    float mx = __builtin_fmaxf(__builtin_fmaxf(s[0][0], s[0][1]), s[0][2]);
+#pragma unroll
+    for (int e = 3; e < 4 * N; e += 2) {
+        const float x = s[e / 4][e % 4];
+        mx = e + 1 < 4 * N ? __builtin_fmaxf(__builtin_fmaxf(mx, x), s[(e + 1) / 4][(e + 1) % 4]) : __builtin_fmaxf(mx, x);
+    }
+    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 16, 64));   // the lanes of the other key groups hold the rest of the row
+    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+    return mx;
 }
 
 template <int N>
@@ -315,15 +325,10 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
                     for (int r = 0; r < 4; ++r)
                         if (key0 + j * kPage + 4 * kg + r > row_pos[nt]) sc[nt][j][r] = kNegInf;
             }
-            float mx = max3(sc[nt][0][0], sc[nt][0][1], sc[nt][0][2]);
-#pragma unroll
-            for (int e = 3; e < 4 * kSP; e += 2)   // two more values per instruction; the odd one out pairs with itself
-                mx = max3(mx, sc[nt][e / 4][e % 4], e + 1 < 4 * kSP ? sc[nt][(e + 1) / 4][(e + 1) % 4] : mx);
-            mx = max3(mx, __shfl_xor(mx, 16, 64), mx);
-            mx = max3(mx, __shfl_xor(mx, 32, 64), mx);
             // the scale is positive, so the maximum can be taken before scaling; mn is finite from the
             // first stage on, because position 0 is visible to every row
-            const float mn = max3(m[nt], mx * p.scale_log2e, m[nt]);
+            const float mx = row_max<kSP>(sc[nt]);
+            const float mn = __builtin_fmaxf(m[nt], mx * p.scale_log2e);
             alpha[nt] = __builtin_amdgcn_exp2f(m[nt] - mn);
             m[nt] = mn;
 #pragma unroll

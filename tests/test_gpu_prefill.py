@@ -147,3 +147,16 @@ def test_random_shapes_and_chunks(torch_cuda, jo):
         ref = jo.prefill_attention(q, w.k_pages, w.v_pages, w.block_table, w.seq_lens, ql, offs)
         got = run_prefill(torch_cuda, w, q, ql, offs, max_q_len=int(max(int(ql.max()), 1)))
         check(got, ref, ql, offs)
+
+
+def test_repeated_calls_are_bitwise_identical(torch_cuda):
+    # nothing in the kernel depends on timing: the same inputs give the same bits, call after call
+    shp = W.Shape("t", 0, 10, 2, 128, 1)
+    lens = np.array([1500, 77, 1030, 2600, 640], dtype=np.int32)
+    ql = np.array([1500, 22, 700, 300, 640], dtype=np.int32)
+    w = W.build(shp, lens, seed=31, cfg=87)
+    q, ql, offs = prefill_inputs(w, ql, seed=32)
+    first = run_prefill(torch_cuda, w, q, ql, offs)
+    for _ in range(4):
+        again = run_prefill(torch_cuda, w, q, ql, offs)
+        assert np.array_equal(first.view(np.uint32), again.view(np.uint32))
