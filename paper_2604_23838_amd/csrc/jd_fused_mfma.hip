@@ -91,7 +91,9 @@ struct Geometry {
 __device__ inline void dma16(unsigned lds_addr, unsigned lane_off, const void* base)
 {
     // LDS[lds_addr + 16 * lane] <- 16 bytes at base + lane_off; counted by vmcnt
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+    // nt: every K/V byte is read once per step, so the load is marked streaming; without it the pages
+    // compete for the caches with themselves and the step is a tenth slower
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
                  :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
 }
 

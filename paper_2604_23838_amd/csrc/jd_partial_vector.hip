@@ -16,6 +16,17 @@
 namespace jd {
 
 namespace {
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+// 16 bytes of K or V, read once per step: a streaming (non-temporal) load
+__device__ inline uint4 load_stream16(const uint16_t* ptr)
+{
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(ptr));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+}  // namespace
+
+
+namespace {
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
@@ -103,8 +114,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void partial_vector_kernel(Par
             const size_t base = static_cast<size_t>(checked_page(p, uniform_load(bt + pg))) * page_elems + lane_off;
 #pragma unroll
             for (int j = 0; j < NL; ++j) {
-                kr[j] = *reinterpret_cast<const uint4*>(p.k_pages + base + j * 512);
-                vr[j] = *reinterpret_cast<const uint4*>(p.v_pages + base + j * 512);
+                kr[j] = load_stream16(p.k_pages + base + j * 512);
+                vr[j] = load_stream16(p.v_pages + base + j * 512);
             }
         }
         for (int i = pg; i < pend; ++i) {
@@ -113,8 +124,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void partial_vector_kernel(Par
                 const size_t base = static_cast<size_t>(checked_page(p, uniform_load(bt + i + 1))) * page_elems + lane_off;
 #pragma unroll
                 for (int j = 0; j < NL; ++j) {
-                    kn[j] = *reinterpret_cast<const uint4*>(p.k_pages + base + j * 512);
-                    vn[j] = *reinterpret_cast<const uint4*>(p.v_pages + base + j * 512);
+                    kn[j] = load_stream16(p.k_pages + base + j * 512);
+                    vn[j] = load_stream16(p.v_pages + base + j * 512);
                 }
             } else {
 #pragma unroll

@@ -9,17 +9,21 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kBlocksPerCu = 2;  // measured best for the read sweep: all CUs move through one 8 MiB window
 
-__global__ __launch_bounds__(kThreads) void stream_read_kernel(const uint4* __restrict__ src, size_t n16, unsigned* sink)
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// Streaming (non-temporal) loads, like the attention kernels' page loads: every byte is read once.
+__global__ __launch_bounds__(kThreads) void stream_read_kernel(const u32x4* __restrict__ src, size_t n16, unsigned* sink)
 {
     const size_t stride = static_cast<size_t>(gridDim.x) * kThreads;
     size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
     unsigned acc = 0;
     for (; i + 3 * stride < n16; i += 4 * stride) {
-        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride),
+                    c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
         acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
     }
     for (; i < n16; i += stride) {
-        const uint4 a = src[i];
+        const u32x4 a = __builtin_nontemporal_load(src + i);
         acc ^= a.x ^ a.y ^ a.z ^ a.w;
     }
     if (acc == 0x9e3779b9u) *sink = acc;  // practically never taken; keeps the loads alive
@@ -46,7 +50,7 @@ jd_status jd_debug_stream_read(const void* src, size_t bytes, void* sink, void* 
 {
     if (!src || !sink || (reinterpret_cast<uintptr_t>(src) & 15u) || bytes < 16) return JD_ERR_INVALID_ARG;
     hipLaunchKernelGGL(stream_read_kernel, dim3(grid_blocks()), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const uint4*>(src), bytes / 16, static_cast<unsigned*>(sink));
+                       static_cast<const u32x4*>(src), bytes / 16, static_cast<unsigned*>(sink));
     return hipGetLastError() == hipSuccess ? JD_OK : JD_ERR_HIP;
 }
 
