@@ -63,9 +63,11 @@ typedef struct {
     int32_t num_pages;         /* NP: pages in k_pages / v_pages; page ids are checked against it */
     float softmax_scale;       /* 0 means 1 / sqrt(D) */
     int32_t variant;           /* a jd_variant */
-    int32_t cu_budget;         /* 0: all compute units; otherwise the number of workgroup slots the partial pass
-                                  may occupy (spatial sharing with a co-located job; Sub-stage Multiplexing,
-                                  "Dynamic Resource Allocation") */
+    int32_t cu_budget;         /* 0: the library's choice (all compute units; three quarters of them for the
+                                  matrix-core variant with head_dim 128, where that already saturates HBM);
+                                  otherwise the number of workgroup slots the partial pass may occupy (spatial
+                                  sharing with a co-located job; Sub-stage Multiplexing, "Dynamic Resource
+                                  Allocation") */
 } jd_config;
 
 /*
