@@ -130,7 +130,7 @@ struct Cursor {
 
 // One planned page-unit: everything issue() needs, with the block-table entry already on its way.
 struct Planned {
-    int meta, dest, id;
+    int meta, dest, id, kv;
     unsigned qrow;
 };
 
@@ -150,6 +150,7 @@ struct Wave {
     unsigned k_src[Geo::kLoadsPerTensor], v_src[Geo::kLoadsPerTensor], q_src[Geo::kQLoads];
     unsigned k_rd[D / 32], v_rd[D / 16], q_rd[D / 32];
     int meta[NS], dest[NS];
+    bool bad_page = false;
     Cursor cur;
     Planned nx, rs[NS];
     // consumer state (lane = query row q = lane % 16; token group tg = lane / 16)
@@ -258,6 +259,7 @@ struct Wave {
         }
         r.meta = mt;
         r.dest = cur.b * p.Hkv + cur.kv;
+        r.kv = cur.kv;
         r.qrow = static_cast<unsigned>(cur.b * p.Hq + cur.kv * p.G);
 
         ++cur.upos;
@@ -275,10 +277,14 @@ struct Wave {
     template <int S>
     __device__ inline void issue(const Planned& r)
     {
-        const int id = checked_page(p, r.id);
+        // a page id out of range reads page 0 and raises the sticky flag when the wave ends; the id stays
+        // on the scalar unit (no divergent branch here)
+        const bool ok = static_cast<unsigned>(r.id) < static_cast<unsigned>(p.NP);
+        bad_page |= !ok;
+        const unsigned id = __builtin_amdgcn_readfirstlane(ok ? static_cast<unsigned>(r.id) : 0u);
         meta[S] = r.meta;
         dest[S] = r.dest;
-        const int kv = r.dest % p.Hkv;
+        const unsigned kv = static_cast<unsigned>(r.kv);
         const unsigned stage = lds_wave + S * Geo::kStageBytes;
         // every read of this stage's previous contents has returned before it is overwritten
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -288,7 +294,7 @@ struct Wave {
 #pragma unroll
             for (int j = 0; j < Geo::kQLoads; ++j) dma16(stage + j * 1024, q_src[j], qb);
         }
-        const uint64_t page_off = static_cast<uint64_t>(static_cast<unsigned>(id * p.Hkv + kv)) << (kRowShift + 4);
+        const uint64_t page_off = static_cast<uint64_t>(id * static_cast<unsigned>(p.Hkv) + kv) << (kRowShift + 4);
         const char* kb = scalar_ptr(reinterpret_cast<const char*>(p.k_pages) + page_off);
         const char* vb = scalar_ptr(reinterpret_cast<const char*>(p.v_pages) + page_off);
 #pragma unroll
@@ -586,6 +592,7 @@ struct Wave {
             if (first_partial) arrive(first_bkv, first_a, first_n);
             if (last_partial) arrive(cur.last_bkv, cur.last_a, cur.last_n);
         }
+        if (bad_page && lane == 0) atomicOr(&p.header[kHdrBadInput], 2);
         JD_STAMP(wave, 6);
     }
 };
