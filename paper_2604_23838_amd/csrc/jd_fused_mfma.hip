@@ -122,6 +122,7 @@ struct Cursor {
     int upos;           // position on the work line
     int r;              // index of the request among those that own pages
     int b, kv, pg;      // request, kv head, page within the request
+    const int32_t* bt;  // block-table row of request b
     int L, n;           // tokens and pages of request b
     int seg_pg0;        // page at which the current segment began
     int seg_at_start;   // the current segment began at the first unit of the span
@@ -232,6 +233,7 @@ struct Wave {
         if (n == 0) n = 1;  // same cause; a one-page request keeps every index in range
         cur.r = r;
         cur.b = b;
+        cur.bt = p.block_table + static_cast<size_t>(b) * p.maxp;
         cur.n = n;
         cur.L = L > n * kPage ? n * kPage : (L < 1 ? 1 : L);
     }
@@ -239,7 +241,17 @@ struct Wave {
     // Describe the unit at the cursor, request its block-table entry, and move the cursor on.
     __device__ inline void plan(Planned& r)
     {
-        r.id = uniform_load(p.block_table + static_cast<size_t>(cur.b) * p.maxp + cur.pg);
+        r.id = uniform_load(cur.bt + cur.pg);
+        r.dest = cur.b * p.Hkv + cur.kv;
+        r.kv = cur.kv;
+        r.qrow = static_cast<unsigned>(cur.b * p.Hq + cur.kv * p.G);
+        // the common case, a full page in the middle of a sequence and of the span: nothing begins or ends
+        if (cur.pg != 0 && cur.pg + 1 != cur.n && cur.upos != u0 && cur.upos + 1 != u1) {
+            r.meta = kPage;
+            ++cur.upos;
+            ++cur.pg;
+            return;
+        }
         const bool first = (cur.upos == u0) || (cur.pg == 0);
         const bool last = (cur.pg == cur.n - 1) || (cur.upos == u1 - 1);
         if (first) {
@@ -258,9 +270,6 @@ struct Wave {
             if (!(cur.seg_at_start && cur.seg_pg0 > 0)) mt |= kMetaSlot1;
         }
         r.meta = mt;
-        r.dest = cur.b * p.Hkv + cur.kv;
-        r.kv = cur.kv;
-        r.qrow = static_cast<unsigned>(cur.b * p.Hq + cur.kv * p.G);
 
         ++cur.upos;
         if (++cur.pg == cur.n) {
@@ -566,6 +575,18 @@ struct Wave {
         if constexpr (S + 1 < NS) round_stage<S + 1>(base, total);
     }
 
+    // A round in which every stage still has a full ring behind it: the wait is the same each time,
+    // a unit is always issued and the next one always planned (no comparisons against the span's end).
+    template <int S>
+    __device__ inline void steady_stage()
+    {
+        wait_vmcnt<(NS - 1) * Geo::kLoadsPerStage>();
+        consume<S>();
+        issue<S>(nx);
+        plan(nx);
+        if constexpr (S + 1 < NS) steady_stage<S + 1>();
+    }
+
     // Request the block-table entries of the first stages, all at once.  Touches no LDS, so it can run
     // while the block is still busy with the partition tables.
     __device__ inline void begin()
@@ -579,7 +600,9 @@ struct Wave {
         issue_stage<0>(total, rs);
         if (NS < total) plan(nx);
         JD_STAMP(wave, 3);
-        for (int base = 0; base < total; base += NS) round_stage<0>(base, total);
+        int base = 0;
+        for (; base + 2 * NS < total; base += NS) steady_stage<0>();
+        for (; base < total; base += NS) round_stage<0>(base, total);
         JD_STAMP(wave, 5);
 
         // pieces of sequences shared with other waves: at most the first and the last stream of the span
@@ -764,6 +787,7 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
     w.cur.upos = w.u0;
     w.cur.r = sr;
     w.cur.b = sb;
+    w.cur.bt = p.block_table + static_cast<size_t>(sb) * p.maxp;
     w.cur.kv = skv;
     w.cur.pg = spg;
     const int L = uniform_load(p.seq_lens + sb);
