@@ -47,6 +47,13 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2604_23838_amd.build); "
                                "there is no fallback implementation")
+        # The library and PyTorch must share one HIP runtime in the process: PyTorch brings its own copy of it,
+        # and if the system's copy were loaded first (as a dependency of this library) the second one to start
+        # would find no device.  With PyTorch imported first the library binds to the copy that is already there.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         l = C.CDLL(LIB_PATH)
         vp = C.c_void_p
         l.jd_validate_config.argtypes = [C.POINTER(jd_config)]
