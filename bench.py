@@ -112,6 +112,16 @@ def main() -> int:
         torch.cuda.synchronize()
     del dst
     op.check_flags()
+    # spread of single steps: an event pair around each of 100 more steps (the records add ~5 us of stream time
+    # to each interval, so these sit a little above the timed region's mean)
+    with torch.cuda.stream(stream):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(100)]
+        for a, b in evs:
+            a.record(stream)
+            op(q, kp, vp, bt, sl, out)
+            b.record(stream)
+        torch.cuda.synchronize()
+    single = np.sort(np.array([a.elapsed_time(b) * 1e3 for a, b in evs]))
     ms_per_step = (t_end - t_start) * 1e3 / args.steps
     kv_bytes = w.kv_bytes
     tbs = kv_bytes / (ms_per_step * 1e-3) / 1e12
@@ -136,6 +146,8 @@ def main() -> int:
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5),
         "us_per_step": round(ms_per_step * 1e3, 2),
+        "single_step_us": {"p10": round(float(single[10]), 2), "median": round(float(single[50]), 2),
+                           "p90": round(float(single[90]), 2), "note": "event pair per step, 100 steps"},
         "pct_of_hbm_peak": round(100.0 * tbs * 1e3 / HBM_PEAK_GBS, 2),
         "stream_read_ceiling_gbs": round(read_ceiling, 1),
         "calibration_copy_bytes": copy_bytes,
@@ -358,6 +370,21 @@ def main() -> int:
                                   "sample": f"first {len(rows)} of {s.batch} requests ({sub.total_tokens} tokens, "
                                             f"{sub.kv_bytes / 1e9:.3f} GB of KV), fp64, {passes} passes, "
                                             f"{dt:.2f}s wall each"}
+        # the same oracle on one core, on the first requests only (a few seconds)
+        rows1, used1 = [], 0.0
+        for b in rows:
+            f = 4.0 * float(w.seq_lens[b]) * s.num_q_heads * s.head_dim
+            if rows1 and used1 + f > 0.25 * args.cpu_seconds * 1.0e9:
+                break
+            rows1.append(b)
+            used1 += f
+        sub1 = W.subset_requests(w, rows1)
+        t1 = time.perf_counter()
+        jo.decode_attention(sub1.q, sub1.k_pages, sub1.v_pages, sub1.block_table, sub1.seq_lens, threads=1)
+        dt1 = time.perf_counter() - t1
+        result["cpu_baseline"]["one_core"] = {"value": round(sub1.kv_bytes / dt1 / 1e12, 6), "unit": "TB/s",
+                                              "sample": f"first {len(rows1)} requests ({sub1.total_tokens} tokens), "
+                                                        f"{dt1:.2f}s wall"}
         result["parity_on_sample"] = {"max_abs": max_abs, "max_rel_floor1e-3": max_rel,
                                       "ok": bool(max_abs <= 5e-3 and max_rel <= 1e-2)}
     op.close()
