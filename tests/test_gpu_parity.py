@@ -322,10 +322,11 @@ def test_hip_graph_capture_and_replay(torch_cuda, jo, variant):
 FULL = {2: "qwen3-8b-like", 3: "stragglers", 4: "qwen3-32b-like", 5: "qwen2.5-0.5b-like"}
 
 
-@pytest.mark.parametrize("cfg", sorted(FULL))
-def test_full_size_configs(torch_cuda, jo, cfg):
-    # the benchmark's workloads at full size, in the launch configuration bench.py times (default variant)
-    w = W.gen_config(cfg, 0)
+@pytest.mark.parametrize("cfg,seed", [(c, 0) for c in sorted(FULL)] + [(2, 1), (3, 2), (5, 1)])
+def test_full_size_configs(torch_cuda, jo, cfg, seed):
+    # the benchmark's workloads at full size, in the launch configuration bench.py times (default variant);
+    # seed 0 is the headline draw, the others are the generator's further draws of lengths and pages
+    w = W.gen_config(cfg, seed)
     got = run_gpu(torch_cuda, arrays(w), 0)
     ref = jo.decode_attention(*arrays(w))
-    check(got, ref, f"cfg{cfg} {FULL[cfg]} default variant")
+    check(got, ref, f"cfg{cfg} {FULL[cfg]} seed {seed} default variant")
