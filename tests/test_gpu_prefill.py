@@ -160,3 +160,33 @@ def test_repeated_calls_are_bitwise_identical(torch_cuda):
     for _ in range(4):
         again = run_prefill(torch_cuda, w, q, ql, offs)
         assert np.array_equal(first.view(np.uint32), again.view(np.uint32))
+
+
+def test_full_size_recompute_on_sampled_tokens(torch_cuda, jo):
+    # The benchmark's prefill workload at full size (the first 32 requests of the cfg2 draw, recomputed whole).
+    # The whole oracle output would take hours, so sampled tokens are checked one by one: token t of a causal
+    # prefill is a decode step over the first t + 1 tokens (pinned on the CPU: a one-token prefill is bitwise the
+    # decode oracle, and later tokens never influence earlier ones).
+    rng = np.random.default_rng(0)
+    lens = W.draw_seq_lens(2, rng)[:32]
+    shp = W.SHAPES[2]
+    w = W.build(W.Shape("p", 0, shp.num_q_heads, shp.num_kv_heads, shp.head_dim, 1), lens, seed=1, cfg=70)
+    ql = lens.copy()
+    q, ql, offs = prefill_inputs(w, ql, seed=2)
+    got = run_prefill(torch_cuda, w, q, ql, offs)
+    pick = np.random.default_rng(3)
+    samples = []
+    for b in range(len(lens)):
+        L = int(lens[b])
+        fixed = [0, 1, 15, 16, 31, 32, 63, 64, 127, 128, L // 2, L - 65, L - 2, L - 1]
+        for t in fixed[:4] + fixed[-4:] if b % 4 else fixed:
+            samples.append((b, min(max(t, 0), L - 1)))
+        for t in pick.integers(0, L, size=3):
+            samples.append((b, int(t)))
+    sb = np.array([s[0] for s in samples]); st = np.array([s[1] for s in samples])
+    q_dec = np.ascontiguousarray(q[offs[sb] + st])                      # [S, Hq, D]
+    bt_dec = np.ascontiguousarray(w.block_table[sb])
+    len_dec = (st + 1).astype(np.int32)
+    ref = jo.decode_attention(q_dec, w.k_pages, w.v_pages, bt_dec, len_dec)
+    ma, mr = error_report(got[offs[sb] + st], ref)
+    assert ma <= ABS_TOL and mr <= REL_TOL, (ma, mr)
