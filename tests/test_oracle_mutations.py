@@ -77,3 +77,53 @@ def test_pins_catch_planted_mistake(name):
                 "sys.exit(0)\n") % (os.path.dirname(here), here, so)
         r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
         assert r.returncode == 3, f"mutant '{name}' was not caught by an assertion (exit {r.returncode}): {r.stdout[-300:]} {r.stderr[-300:]}"
+
+
+# ---- the prefill oracle: the same exercise with its own pins ----
+import test_oracle_prefill_pins as ppins
+
+PREFILL_MUTATIONS = {
+    "prefill: own position not visible": ("int last = c + t; /* attends to positions 0 .. last */", "int last = c + t - 1;"),
+    "prefill: sees one token of the future": ("int last = c + t; /* attends to positions 0 .. last */", "int last = c + t + 1 < L ? c + t + 1 : L - 1;"),
+    "prefill: context length ignored": ("int n = q_lens[b], c = L - n, kv = h / G;", "int n = q_lens[b], c = 0, kv = h / G;"),
+    "prefill: query row ignores the offset": ("int64_t row = (int64_t)q_offsets[b] + t;", "int64_t row = (int64_t)t;"),
+    "prefill: kv head by modulo": ("int n = q_lens[b], c = L - n, kv = h / G;", "int n = q_lens[b], c = L - n, kv = h % Hkv;"),
+    "prefill: weights not normalised": ("double wj = w[j] / z;", "double wj = w[j];"),
+    "prefill: scale dropped": ("w[j] = p.scale * s;", "w[j] = s;"),
+}
+
+
+def run_prefill_pins(jo):
+    ppins.test_single_new_token_is_decode_attention(jo)
+    ppins.test_matches_torch_sdpa_with_causal_mask_float64(jo)
+    ppins.test_first_token_of_a_full_prefill_returns_v0_and_future_tokens_do_not_matter(jo)
+    ppins.test_chunked_prefill_equals_one_shot(jo)
+    ppins.test_malformed_arguments_are_rejected(jo)
+
+
+def test_unmutated_prefill_oracle_passes(jo):
+    run_prefill_pins(jo)
+
+
+@pytest.mark.parametrize("name", sorted(PREFILL_MUTATIONS))
+def test_prefill_pins_catch_planted_mistake(name):
+    old, new = PREFILL_MUTATIONS[name]
+    src = open(SRC).read()
+    assert src.count(old) >= 1, f"mutation site for '{name}' not found"
+    here = os.path.dirname(os.path.abspath(__file__))
+    with tempfile.TemporaryDirectory() as tmp:
+        c = os.path.join(tmp, "mutant.c")
+        so = os.path.join(tmp, "mutant.so")
+        open(c, "w").write(src.replace(old, new, 1))
+        subprocess.check_call(["gcc", "-O1", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-o", so, c, "-lm"])
+        code = ("import sys; sys.path[:0] = [%r, %r]\n"
+                "from oracle import jo\n"
+                "import test_oracle_mutations as t\n"
+                "jo._lib = jo.load_library(%r)\n"
+                "try:\n"
+                "    t.run_prefill_pins(jo)\n"
+                "except (AssertionError, ValueError, FloatingPointError) as e:\n"
+                "    print('caught:', type(e).__name__); sys.exit(3)\n"
+                "sys.exit(0)\n") % (os.path.dirname(here), here, so)
+        r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+        assert r.returncode == 3, f"mutant '{name}' was not caught by an assertion (exit {r.returncode}): {r.stdout[-300:]} {r.stderr[-300:]}"
