@@ -364,8 +364,7 @@ struct Wave {
             }
         }
         float mx = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        mx = rows_max(mx);
         const float mn = fmaxf(m, mx);  // finite: every page holds at least one live token
         const float alpha = __builtin_amdgcn_exp2f(m - mn);
         float pr[4];
@@ -401,9 +400,7 @@ struct Wave {
     __device__ inline void finalize(int mt, int bkv)
     {
         const int qh = lane & 15, tg = lane >> 4;
-        float lt = l;
-        lt += __shfl_xor(lt, 16, 64);
-        lt += __shfl_xor(lt, 32, 64);
+        const float lt = rows_sum(l);
         if (qh >= p.G) return;
         const int b = bkv / p.Hkv, kv = bkv % p.Hkv;
         if (mt & kMetaComplete) {

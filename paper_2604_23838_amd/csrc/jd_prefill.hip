@@ -68,8 +68,7 @@ __device__ inline float row_max(const f32x4 (&s)[N])
         const float x = s[e / 4][e % 4];
         mx = e + 1 < 4 * N ? __builtin_fmaxf(__builtin_fmaxf(mx, x), s[(e + 1) / 4][(e + 1) % 4]) : __builtin_fmaxf(mx, x);
     }
-    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 16, 64));   // the lanes of the other key groups hold the rest of the row
-    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+    mx = rows_max(mx);   // the lanes of the other key groups hold the rest of the row
     return mx;
 }
 

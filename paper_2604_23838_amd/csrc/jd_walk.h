@@ -13,6 +13,30 @@ __device__ inline T uniform_load(const T* ptr)
 }
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+// Reductions over the four lanes {l, l^16, l^32, l^48}: the four 16-lane rows of a wave hold the
+// four slices of one column of a 16x16 matrix-core result.  A row swap exchanges rows between two
+// registers inside the vector ALU (after it, the two registers hold a lane's own value and its
+// partner's, in either order), so the chain never waits on the LDS crossbar that a general
+// cross-lane shuffle goes through.  max and + are commutative: the result has the shuffle's bits.
+__device__ inline float rows_max(float x)
+{
+    const unsigned xb = __float_as_uint(x);
+    const u32x2 a = __builtin_amdgcn_permlane16_swap(xb, xb, false, false);
+    const unsigned yb = __float_as_uint(__builtin_fmaxf(__uint_as_float(a.x), __uint_as_float(a.y)));
+    const u32x2 b = __builtin_amdgcn_permlane32_swap(yb, yb, false, false);
+    return __builtin_fmaxf(__uint_as_float(b.x), __uint_as_float(b.y));
+}
+
+__device__ inline float rows_sum(float x)
+{
+    const unsigned xb = __float_as_uint(x);
+    const u32x2 a = __builtin_amdgcn_permlane16_swap(xb, xb, false, false);
+    const unsigned yb = __float_as_uint(__uint_as_float(a.x) + __uint_as_float(a.y));
+    const u32x2 b = __builtin_amdgcn_permlane32_swap(yb, yb, false, false);
+    return __uint_as_float(b.x) + __uint_as_float(b.y);
+}
 
 struct Stream {
     int b;  // request
