@@ -77,14 +77,17 @@ typedef struct {
 jd_status jd_validate_config(const jd_config *cfg);
 
 /*
- * Bytes of device workspace a handle for `cfg` holds (work-partition tables and split-KV
- * partial states).  Pure host function; 0 if cfg is invalid.
+ * Bytes of device workspace a handle for `cfg` holds on a 256-compute-unit device (work-partition
+ * tables and split-KV partial states; a device with fewer units needs less).  Pure host function;
+ * 0 if cfg is invalid.
  */
 size_t jd_workspace_bytes(const jd_config *cfg);
 
 /*
  * Create a handle on the current HIP device.  Validates cfg (no GPU touched on failure),
- * then allocates the workspace once with hipMalloc.  *out is set only on JD_OK.
+ * then allocates the workspace once with hipMalloc.  *out is set only on JD_OK.  Every later
+ * call that takes the handle must be made with that device current (JD_ERR_INVALID_ARG
+ * otherwise).  A handle is not thread-safe: calls on one handle come from one thread at a time.
  */
 jd_status jd_create(const jd_config *cfg, jd_handle **out);
 

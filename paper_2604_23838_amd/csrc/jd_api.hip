@@ -105,7 +105,29 @@ int wave_slots(int variant, int cus)
 
 constexpr int kAssumedCus = 256;  // MI355X; used only by the pure-host size query
 
+// Compute units a handle spreads the partial pass over, of `device_cus` present.
+int effective_cus(const jd_config& c, int variant, int device_cus)
+{
+    if (c.cu_budget > 0) return c.cu_budget < device_cus ? c.cu_budget : device_cus;
+    // measured: with 128-wide heads three quarters of the compute units already keep HBM saturated,
+    // and the step is 2-3 % faster without the contention of the rest (which stay free for a co-located job)
+    if (variant == JD_VARIANT_MFMA && c.head_dim == 128) return device_cus * 3 / 4;
+    return device_cus;
+}
+
 bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+bool misaligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) != 0; }
+
+// The workspace and the kernels' launches belong to the device the handle was created on.
+jd_status check_device(jd_handle* h)
+{
+    int dev = -1;
+    const hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(h, JD_ERR_HIP, std::string("hipGetDevice failed: ") + hipGetErrorString(e));
+    if (dev != h->device)
+        return fail(h, JD_ERR_INVALID_ARG, "the current HIP device is not the one the handle was created on");
+    return JD_OK;
+}
 
 }  // namespace
 
@@ -123,8 +145,8 @@ size_t jd_workspace_bytes(const jd_config* cfg)
 {
     std::string msg;
     if (validate(cfg, msg) != JD_OK) return 0;
-    const int cus = cfg->cu_budget > 0 ? cfg->cu_budget : kAssumedCus;
-    return make_layout(*cfg, wave_slots(resolve_variant(*cfg), cus)).total;
+    const int variant = resolve_variant(*cfg);
+    return make_layout(*cfg, wave_slots(variant, effective_cus(*cfg, variant, kAssumedCus))).total;
 }
 
 jd_status jd_create(const jd_config* cfg, jd_handle** out)
@@ -147,14 +169,7 @@ jd_status jd_create(const jd_config* cfg, jd_handle** out)
     h->cfg = *cfg;
     h->device = dev;
     h->variant = resolve_variant(*cfg);
-    int cus = prop.multiProcessorCount;
-    if (cfg->cu_budget > 0) {
-        if (cfg->cu_budget < cus) cus = cfg->cu_budget;
-    } else if (h->variant == JD_VARIANT_MFMA && cfg->head_dim == 128) {
-        // measured: with 128-wide heads three quarters of the compute units already keep HBM saturated,
-        // and the step is 2-3 % faster without the contention of the rest (which stay free for a co-located job)
-        cus = cus * 3 / 4;
-    }
+    const int cus = effective_cus(*cfg, h->variant, prop.multiProcessorCount);
     const int slots = wave_slots(h->variant, cus);
     const Layout lay = make_layout(*cfg, slots);
     h->workspace_bytes = lay.total;
@@ -193,8 +208,9 @@ jd_status jd_decode_attention(jd_handle* h, const void* q, const void* k_pages, 
         return fail(h, JD_ERR_INVALID_ARG, "q, k_pages, v_pages, block_table, seq_lens and out must be non-NULL");
     if (misaligned(q) || misaligned(k_pages) || misaligned(v_pages) || misaligned(out))
         return fail(h, JD_ERR_INVALID_ARG, "q, k_pages, v_pages and out must be 16-byte aligned");
-    if (reinterpret_cast<uintptr_t>(block_table) & 3u || reinterpret_cast<uintptr_t>(seq_lens) & 3u)
+    if (misaligned4(block_table) || misaligned4(seq_lens))
         return fail(h, JD_ERR_INVALID_ARG, "block_table and seq_lens must be 4-byte aligned");
+    if (jd_status st = check_device(h)) return st;
     jd::Params p = h->params;
     p.q = static_cast<const uint16_t*>(q);
     p.k_pages = static_cast<const uint16_t*>(k_pages);
@@ -224,6 +240,9 @@ jd_status jd_append_kv(jd_handle* h, const void* k_new, const void* v_new, void*
         return fail(h, JD_ERR_INVALID_ARG, "k_new, v_new, k_pages, v_pages, block_table and seq_lens must be non-NULL");
     if (misaligned(k_new) || misaligned(v_new) || misaligned(k_pages) || misaligned(v_pages))
         return fail(h, JD_ERR_INVALID_ARG, "k_new, v_new, k_pages and v_pages must be 16-byte aligned");
+    if (misaligned4(block_table) || misaligned4(seq_lens) || misaligned4(active))
+        return fail(h, JD_ERR_INVALID_ARG, "block_table, seq_lens and active must be 4-byte aligned");
+    if (jd_status st = check_device(h)) return st;
     jd::Params p = h->params;
     p.block_table = block_table;
     hipError_t e = jd::launch_append_kv(p, static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
@@ -242,7 +261,10 @@ jd_status jd_prefill_attention(jd_handle* h, const void* q, const void* k_pages,
         return fail(h, JD_ERR_INVALID_ARG, "q, k_pages, v_pages, block_table, seq_lens, q_lens, q_offsets and out must be non-NULL");
     if (misaligned(q) || misaligned(k_pages) || misaligned(v_pages) || misaligned(out))
         return fail(h, JD_ERR_INVALID_ARG, "q, k_pages, v_pages and out must be 16-byte aligned");
+    if (misaligned4(block_table) || misaligned4(seq_lens) || misaligned4(q_lens) || misaligned4(q_offsets))
+        return fail(h, JD_ERR_INVALID_ARG, "block_table, seq_lens, q_lens and q_offsets must be 4-byte aligned");
     if (max_q_len < 0) return fail(h, JD_ERR_INVALID_ARG, "max_q_len must be >= 0");
+    if (jd_status st = check_device(h)) return st;
     jd::Params p = h->params;
     // a request never has more new tokens than its table holds; the launch is sized for the bound
     const int64_t cap = static_cast<int64_t>(p.maxp) * jd::kPage;
@@ -263,6 +285,7 @@ jd_status jd_prefill_attention(jd_handle* h, const void* q, const void* k_pages,
 jd_status jd_check_device_flags(jd_handle* h, void* stream)
 {
     if (!h) return fail(nullptr, JD_ERR_INVALID_ARG, "handle is NULL");
+    if (jd_status st = check_device(h)) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     int32_t flag = 0;
     hipError_t e = hipMemcpyAsync(&flag, h->params.header + jd::kHdrBadInput, sizeof flag, hipMemcpyDeviceToHost, s);
@@ -284,6 +307,7 @@ jd_status jd_debug_partition(jd_handle* h, const int32_t* seq_lens, int32_t* hea
 {
     if (!h) return fail(nullptr, JD_ERR_INVALID_ARG, "handle is NULL");
     if (!seq_lens) return fail(h, JD_ERR_INVALID_ARG, "seq_lens is NULL");
+    if (jd_status st = check_device(h)) return st;
     jd::Params p = h->params;
     p.seq_lens = seq_lens;
     hipStream_t s = static_cast<hipStream_t>(stream);

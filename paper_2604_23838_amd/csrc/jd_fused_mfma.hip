@@ -58,9 +58,11 @@ constexpr int kWaves = JD_MFMA_WAVES;  // waves per block; one block per compute
 constexpr int kLdsBudget = 160 * 1024;
 
 #ifdef JD_TIMING
-// Development aid (not built by default): per-wave phase time stamps of the constant 100 MHz clock.
+// Development aid (not built by default): per-wave phase time stamps of the constant 100 MHz clock;
+// slot 7 holds the number of the die (XCC_ID register) the wave ran on.
 __device__ long long g_stamps[kMaxWaveSlots][8];
-#define JD_STAMP(w, i) do { if ((threadIdx.x & 63) == 0) g_stamps[(w)][(i)] = wall_clock64(); } while (0)
+#define JD_STAMP(w, i) do { if ((threadIdx.x & 63) == 0) { g_stamps[(w)][(i)] = wall_clock64(); \
+    if ((i) == 0) g_stamps[(w)][7] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11)); } } while (0)
 #else
 #define JD_STAMP(w, i) do { } while (0)
 #endif

@@ -214,6 +214,45 @@ def test_bad_page_id_is_flagged_not_dereferenced(torch_cuda):
         assert e.value.status == jb.JD_ERR_BAD_INPUT
 
 
+def test_misaligned_and_null_arguments_are_refused_before_any_launch(torch_cuda):
+    """Every refusal below happens on the host; the addresses are never handed to a kernel."""
+    torch = torch_cuda
+    from paper_2604_23838_amd import binding as jb
+    cfg = jb.jd_config(batch=2, num_q_heads=4, num_kv_heads=2, head_dim=64, page_size=16, max_pages_per_seq=4,
+                       num_pages=8, softmax_scale=0.0, variant=0, cu_budget=0)
+    h = jb.jd_create(cfg)
+    try:
+        buf = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+        a = buf.data_ptr()
+        assert a % 16 == 0
+        ok = dict(q=a, k=a + 4096, v=a + 8192, bt=a + 12288, sl=a + 16384, out=a + 20480, ql=a + 24576, qo=a + 28672)
+        for bad in ("q", "k", "v", "out"):
+            args = dict(ok); args[bad] += 8
+            with pytest.raises(jb.JdError) as e:
+                jb.jd_decode_attention(h, args["q"], args["k"], args["v"], args["bt"], args["sl"], args["out"])
+            assert e.value.status == jb.JD_ERR_INVALID_ARG, bad
+        for bad in ("bt", "sl"):
+            args = dict(ok); args[bad] += 2
+            with pytest.raises(jb.JdError) as e:
+                jb.jd_decode_attention(h, args["q"], args["k"], args["v"], args["bt"], args["sl"], args["out"])
+            assert e.value.status == jb.JD_ERR_INVALID_ARG, bad
+        for bad in ("bt", "sl", "ql", "qo"):
+            args = dict(ok); args[bad] += 2
+            with pytest.raises(jb.JdError) as e:
+                jb.jd_prefill_attention(h, args["q"], args["k"], args["v"], args["bt"], args["sl"], args["ql"],
+                                        args["qo"], 16, args["out"])
+            assert e.value.status == jb.JD_ERR_INVALID_ARG, bad
+        with pytest.raises(jb.JdError) as e:
+            jb.jd_append_kv(h, ok["q"], ok["q"], ok["k"], ok["v"], ok["bt"], ok["sl"] + 2)
+        assert e.value.status == jb.JD_ERR_INVALID_ARG
+        with pytest.raises(jb.JdError) as e:
+            jb.jd_decode_attention(h, ok["q"], None, ok["v"], ok["bt"], ok["sl"], ok["out"])
+        assert e.value.status == jb.JD_ERR_INVALID_ARG
+        assert "non-NULL" in str(e.value)
+    finally:
+        jb.jd_destroy(h)
+
+
 def test_random_shapes(torch_cuda, jo):
     # a seeded sweep over head layouts, group sizes up to 16, both head sizes and mixed length patterns
     rng = np.random.default_rng(2024)
