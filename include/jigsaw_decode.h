@@ -150,7 +150,9 @@ jd_status jd_append_kv(jd_handle *h, const void *k_new, const void *v_new, void 
  *   max_q_len   host value: an upper bound of q_lens (it sizes the launch; tokens beyond it are not computed)
  *   out         fp32 [TQ, Hq, D]           device, 16-byte aligned; the rows of the new tokens are written,
  *                                          all others are left untouched
- * With n = 1 for every request the result is that of jd_decode_attention.  Only enqueues on `stream`.
+ * With n = 1 for every request the result is that of jd_decode_attention.  Only enqueues on `stream`
+ * (no allocation, no host synchronisation), so it may be captured into a HIP graph; a captured launch is
+ * sized by the max_q_len given at capture time.  Uses the handle's workspace like the other calls.
  * Bound by the matrix cores rather than by HBM; same input checks and flags as jd_decode_attention.
  */
 jd_status jd_prefill_attention(jd_handle *h, const void *q, const void *k_pages, const void *v_pages,

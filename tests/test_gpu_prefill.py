@@ -162,6 +162,51 @@ def test_repeated_calls_are_bitwise_identical(torch_cuda):
         assert np.array_equal(first.view(np.uint32), again.view(np.uint32))
 
 
+def test_hip_graph_capture_and_replay(torch_cuda, jo):
+    # the call only enqueues two kernels: it can be captured, and every replay (eager work and synchronisations in
+    # between, new chunk lengths written into the captured buffers) must match the oracle
+    from paper_2604_23838_amd import binding as jb
+    torch = torch_cuda
+    shp = W.Shape("t", 0, 12, 4, 128, 1)
+    lens = np.array([900, 130, 2049, 64, 555], dtype=np.int32)
+    w = W.build(shp, lens, seed=41, cfg=88)
+    cap = 600                                     # the captured launch is sized for chunks of up to 600 tokens
+    q, _, _ = prefill_inputs(w, np.full(len(lens), cap, dtype=np.int32), seed=42)
+    offs = (np.arange(len(lens)) * cap).astype(np.int32)
+    op = jb.DecodeAttention(len(lens), shp.num_q_heads, shp.num_kv_heads, shp.head_dim, w.max_pages_per_seq, w.num_pages)
+    tq, tk, tv = bf16_dev(torch, q), bf16_dev(torch, w.k_pages), bf16_dev(torch, w.v_pages)
+    tbt, tl = torch.from_numpy(w.block_table).to("cuda:0"), torch.from_numpy(w.seq_lens).to("cuda:0")
+    ql = np.minimum(lens, [600, 100, 300, 64, 1]).astype(np.int32)
+    tql, tof = torch.from_numpy(ql).to("cuda:0"), torch.from_numpy(offs).to("cuda:0")
+    out = torch.full(q.shape, 777.0, dtype=torch.float32, device="cuda:0")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        op.prefill(tq, tk, tv, tbt, tl, tql, tof, cap, out=out)      # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    eager = out.cpu().numpy().copy()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        op.prefill(tq, tk, tv, tbt, tl, tql, tof, cap, out=out)
+    rng = np.random.default_rng(5)
+    for rep in range(4):
+        if rep:
+            ql = np.minimum(lens, rng.integers(0, cap + 1, size=len(lens))).astype(np.int32)
+            tql.copy_(torch.from_numpy(ql))
+        out.fill_(777.0)                          # eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        ref = jo.prefill_attention(q, w.k_pages, w.v_pages, w.block_table, w.seq_lens, ql, offs)
+        check(got, ref, ql, offs)
+        if rep == 0:
+            assert np.array_equal(got.view(np.uint32), eager.view(np.uint32))
+    op.check_flags()
+    op.close()
+
+
 def test_full_size_recompute_on_sampled_tokens(torch_cuda, jo):
     # The benchmark's prefill workload at full size (the first 32 requests of the cfg2 draw, recomputed whole).
     # The whole oracle output would take hours, so sampled tokens are checked one by one: token t of a causal
