@@ -732,15 +732,7 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
     if (group < active && !partition_only)
         warm = uniform_load(p.block_table + static_cast<size_t>(sb) * p.maxp + spg) ^ uniform_load(p.seq_lens + sb);
 
-    if (!partition_only) {
-        // rows of requests without tokens
-        for (int b = blockIdx.x; b < p.B; b += gridDim.x) {
-            if (pages_of(p, p.seq_lens[b]) == 0) {
-                float* o = p.out + static_cast<size_t>(b) * p.Hq * D;
-                for (int i = threadIdx.x; i < p.Hq * D; i += kThreads) o[i] = 0.f;
-            }
-        }
-    } else {
+    if (partition_only) {
         // tables for inspection
         if (blockIdx.x == 0) {
             for (int b = threadIdx.x; b <= p.B; b += kThreads) {
@@ -764,9 +756,21 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
             reinterpret_cast<i32x4*>(p.wave_start)[wave] = ws;
         }
     }
-    __syncthreads();  // the scratch is dead from here on, and this block's copy of the request list is stored
-    if (partition_only || group >= active) return;
+    // Every wave's stores of the request list have reached the L2 before the barrier, so after it the whole
+    // block's copy is there for the scalar loads that walk it (the barrier alone does not wait for stores).
     asm volatile("s_waitcnt vmcnt(0)" :: "s"(warm) : "memory");
+    __syncthreads();  // the scratch is dead from here on
+    if (!partition_only) {
+        // Rows of requests without tokens.  Nobody waits for these stores: they drain while the page ring
+        // starts (older operations in flight only make the ring's counter waits err on the safe side).
+        for (int b = blockIdx.x; b < p.B; b += gridDim.x) {
+            if (pages_of(p, uniform_load(p.seq_lens + b)) == 0) {
+                float4* o = reinterpret_cast<float4*>(p.out + static_cast<size_t>(b) * p.Hq * D);
+                for (int i = threadIdx.x; i < p.Hq * D / 4; i += kThreads) o[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+    }
+    if (partition_only || group >= active) return;
     JD_STAMP(wave, 2);
 
     W w(p);
