@@ -58,9 +58,11 @@ constexpr int kWaves = JD_MFMA_WAVES;  // waves per block; one block per compute
 constexpr int kLdsBudget = 160 * 1024;
 
 #ifdef JD_TIMING
-// Development aid (not built by default): per-wave phase time stamps of the constant 100 MHz clock;
-// slot 7 holds the number of the die (XCC_ID register) the wave ran on.
-__device__ long long g_stamps[kMaxWaveSlots][8];
+// Development aid (not built by default): per-wave phase time stamps of the constant 100 MHz clock.
+// Slots: 0 entry, 1 tables built, 2 prologue done, 3 first pages requested, 5 last page consumed, 4 record
+// stores complete, 8 first arrival done, 9/10 around the last merge the wave did, 6 done; slot 7 holds the
+// number of the die (XCC_ID register) the wave ran on.
+__device__ long long g_stamps[kMaxWaveSlots][12];
 #define JD_STAMP(w, i) do { if ((threadIdx.x & 63) == 0) { g_stamps[(w)][(i)] = wall_clock64(); \
     if ((i) == 0) g_stamps[(w)][7] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11)); } } while (0)
 #else
@@ -463,7 +465,9 @@ struct Wave {
         if (old != w1 - w0) return;
         if (lane == 0) __hip_atomic_store(p.counters + bkv, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         asm volatile("" ::: "memory");  // the record loads below stay behind the counter read
+        JD_STAMP(wave, 9);
         merge(bkv, a, w0, w1);
+        JD_STAMP(wave, 10);
     }
 
     // Log-sum-exp merge of the pieces of one stream, by one wave.  The G*D accumulator floats of a
@@ -611,7 +615,9 @@ struct Wave {
         if (first_partial || last_partial) {
             // release: the write-through record stores of this wave have completed before it is counted
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            JD_STAMP(wave, 4);
             if (first_partial) arrive(first_bkv, first_a, first_n);
+            JD_STAMP(wave, 8);
             if (last_partial) arrive(cur.last_bkv, cur.last_a, cur.last_n);
         }
         if (bad_page && lane == 0) atomicOr(&p.header[kHdrBadInput], 2);
@@ -834,7 +840,7 @@ int mfma_waves_per_block() { return kWaves; }
 #ifdef JD_TIMING
 extern "C" int jd_debug_read_stamps(long long* host)
 {
-    return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_stamps), sizeof(long long) * kMaxWaveSlots * 8) == hipSuccess ? 0 : 1;
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_stamps), sizeof(long long) * kMaxWaveSlots * 12) == hipSuccess ? 0 : 1;
 }
 #endif
 
