@@ -113,6 +113,23 @@ def test_wide_batch_of_short_requests(torch_cuda, jo, variant):
     check(run_gpu(torch_cuda, arrays(w), variant), ref, f"wide batch v{variant}")
 
 
+def test_largest_supported_batch(torch_cuda, jo):
+    # the fused kernel keeps its partition tables in LDS, which bounds the batch at 8192 rows: all of them
+    # live here, short, ragged, with a few long ones in between; one row more is refused at creation
+    from paper_2604_23838_amd import binding as jb
+    rng = np.random.default_rng(21)
+    lens = rng.integers(1, 40, size=8192).astype(np.int32)
+    lens[[5, 4000, 8191]] = [3000, 1500, 2049]
+    w = W.build(W.SHAPES[5], lens, seed=21, cfg=92)
+    ref = jo.decode_attention(*arrays(w))
+    check(run_gpu(torch_cuda, arrays(w), 2), ref, "largest batch")
+    s = W.SHAPES[5]
+    cfg = jb.jd_config(8193, s.num_q_heads, s.num_kv_heads, s.head_dim, 16, 4, 64, 0.0, jb.JD_VARIANT_MFMA, 0)
+    with pytest.raises(jb.JdError) as e:
+        jb.jd_create(cfg)
+    assert e.value.status == jb.JD_ERR_UNSUPPORTED
+
+
 @pytest.mark.parametrize("variant", VARIANTS)
 def test_stragglers_scattered_in_a_finished_batch(torch_cuda, jo, variant):
     # a big batch in which all but a few requests have finished: the walk from one live request to the next

@@ -162,6 +162,20 @@ def test_repeated_calls_are_bitwise_identical(torch_cuda):
         assert np.array_equal(first.view(np.uint32), again.view(np.uint32))
 
 
+def test_wide_batch_of_tiny_chunks(torch_cuda, jo):
+    # thousands of requests with zero to a few new tokens each: the ranking kernel runs over many tiles and
+    # most blocks of the launch have a single, mostly padded, tile of rows
+    rng = np.random.default_rng(61)
+    B = 2500
+    lens = rng.integers(0, 90, size=B).astype(np.int32)
+    ql = np.minimum(lens, rng.integers(0, 4, size=B)).astype(np.int32)
+    w = W.build(W.Shape("t", 0, 14, 2, 64, 1), lens, seed=61, cfg=86)
+    q, ql, offs = prefill_inputs(w, ql, seed=62)
+    ref = jo.prefill_attention(q, w.k_pages, w.v_pages, w.block_table, w.seq_lens, ql, offs)
+    got = run_prefill(torch_cuda, w, q, ql, offs, max_q_len=3)
+    check(got, ref, ql, offs)
+
+
 def test_hip_graph_capture_and_replay(torch_cuda, jo):
     # the call only enqueues two kernels: it can be captured, and every replay (eager work and synchronisations in
     # between, new chunk lengths written into the captured buffers) must match the oracle
