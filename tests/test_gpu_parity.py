@@ -113,6 +113,26 @@ def test_wide_batch_of_short_requests(torch_cuda, jo, variant):
     check(run_gpu(torch_cuda, arrays(w), variant), ref, f"wide batch v{variant}")
 
 
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_one_very_long_sequence_cut_into_many_pieces(torch_cuda, jo, variant):
+    # 131 071 tokens in one request: each of its kv heads is cut over about a hundred waves, so the merge of the
+    # pieces runs over several batches of records; the short neighbour shares the first wave with it
+    lens = np.array([131071, 40], dtype=np.int32)
+    w = W.build(W.SHAPES[2], lens, seed=23, cfg=91)
+    ref = jo.decode_attention(*arrays(w))
+    check(run_gpu(torch_cuda, arrays(w), variant), ref, f"very long v{variant}")
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(14, 2, 64), (64, 4, 128), (8, 8, 128), (6, 6, 64), (16, 1, 128)])
+def test_long_sequences_on_every_record_size(torch_cuda, jo, hq, hkv, d):
+    # the merge of many pieces with 1, 2 and 4 KiB query slots (its batch size depends on it), group sizes 1 to 16
+    # and wave groups of 1, 2 and 4
+    lens = np.array([7, 50000, 0, 33000], dtype=np.int32)
+    w = W.build(W.Shape("t", 0, hq, hkv, d, 1), lens, seed=24, cfg=90)
+    ref = jo.decode_attention(*arrays(w))
+    check(run_gpu(torch_cuda, arrays(w), 2), ref, f"long sequences {hq}/{hkv}/{d}")
+
+
 def test_largest_supported_batch(torch_cuda, jo):
     # the fused kernel keeps its partition tables in LDS, which bounds the batch at 8192 rows: all of them
     # live here, short, ragged, with a few long ones in between; one row more is refused at creation
