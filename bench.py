@@ -1,15 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of libjigsaw_decode: paged decode attention on one MI355X.
 
-A step is one jd_decode_attention call (work partition + split-KV partial pass + combine) over
-one synthetic decode batch that is already resident in HBM.  The default workload is the
-long-tailed Qwen3-8B-like rollout step (batch 256, 32 q / 8 kv heads, head_dim 128, 16-token
-pages, 512-token prompt + lognormal response); `--cfg` selects another of the five configs.
+A step is one jd_decode_attention call (work partition + split-KV partial pass + combine, one
+launch) over one synthetic decode batch that is already resident in HBM.  The headline workload
+is the long-tailed Qwen3-8B-like rollout step (batch 256, 32 q / 8 kv heads, head_dim 128,
+16-token pages, 512-token prompt + lognormal response); `--cfg` selects another of the five configs.
 
 Prints ONE JSON line: the metric (KV bytes read per second, i.e. T * 2 * Hkv * D * 2 bytes per
-step over the step time), a `roofline` object for the dominant kernel (the partial pass, timed
-with HIP events on the launch stream inside the timed region), and a `cpu_baseline` object (the
-fp64 CPU oracle timed on the host cores on a bounded sample of the same workload).
+step over the step time), a `roofline` object for the decode kernel (timed with HIP events on the
+launch stream inside the timed region), a `cpu_baseline` object (the fp64 CPU oracle timed on
+the host cores on a bounded sample of the same workload) and, for the default workload, a
+`configs` array with the other timed configurations, the merged-straggler batch and the prefill
+of a new turn, each with its own step time, roofline fraction and sampled parity against the oracle.
 """
 from __future__ import annotations
 
@@ -23,7 +25,13 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E peak
+MFMA_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix peak
+MAX_ABS, MAX_REL = 5e-3, 1e-2
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
 def main() -> int:
@@ -33,8 +41,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--cfg", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--variant", type=int, default=0, help="0 default, 1 vector, 2 mfma")
     ap.add_argument("--cu-budget", type=int, default=0)
+    ap.add_argument("--vector-kernels", action="store_true",
+                    help="time the vector-ALU comparison kernels instead of the product call")
+    ap.add_argument("--headline-only", action="store_true", help="skip the `configs` array (profiler runs)")
     ap.add_argument("--sweep", choices=["none", "cu", "batch", "merge", "loop", "prefill"], default="none",
                     help="extra measurements after the timed region: 'cu' = step time at 25/50/75/100 %% of the "
                          "compute units (the library's cu_budget), 'batch' = step time as the batch shrinks to its "
@@ -59,36 +69,72 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     dev = torch.device("cuda:0")
-    t0 = time.time()
-    w = W.gen_config(args.cfg, args.seed, threads=min(16, os.cpu_count() or 8))
-    s = w.shape
-    print(f"[bench] generated cfg{args.cfg} ({s.name}) T={w.total_tokens} KV={w.kv_bytes / 1e9:.3f} GB "
-          f"in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
-    q = torch.from_numpy(w.q.view(np.int16)).to(dev).view(torch.bfloat16)
-    kp = torch.from_numpy(w.k_pages.view(np.int16)).to(dev).view(torch.bfloat16)
-    vp = torch.from_numpy(w.v_pages.view(np.int16)).to(dev).view(torch.bfloat16)
-    bt = torch.from_numpy(w.block_table).to(dev)
-    sl = torch.from_numpy(w.seq_lens).to(dev)
-    out = torch.empty((s.batch, s.num_q_heads, s.head_dim), dtype=torch.float32, device=dev)
-    op = jb.DecodeAttention(s.batch, s.num_q_heads, s.num_kv_heads, s.head_dim, w.max_pages_per_seq, w.num_pages,
-                            variant=args.variant, cu_budget=args.cu_budget)
+    threads = min(16, os.cpu_count() or 8)
     stream = torch.cuda.Stream()
-    with torch.cuda.stream(stream):
-        for _ in range(args.warmup):
-            op(q, kp, vp, bt, sl, out)
-        torch.cuda.synchronize()
-        # HIP events around the kernels of every 8th step of the timed region (an event record costs
-        # stream time, so timing every step would slow down the very steps being measured)
+
+    def upload(w):
+        return (torch.from_numpy(w.q.view(np.int16)).to(dev).view(torch.bfloat16),
+                torch.from_numpy(w.k_pages.view(np.int16)).to(dev).view(torch.bfloat16),
+                torch.from_numpy(w.v_pages.view(np.int16)).to(dev).view(torch.bfloat16),
+                torch.from_numpy(w.block_table).to(dev), torch.from_numpy(w.seq_lens).to(dev))
+
+    def make_op(w, cu_budget=0):
+        s_ = w.shape
+        return jb.DecodeAttention(s_.batch, s_.num_q_heads, s_.num_kv_heads, s_.head_dim, w.max_pages_per_seq,
+                                  w.num_pages, cu_budget=cu_budget)
+
+    def timed_region(o, t, out_, steps, warmup, vector=False):
+        """`warmup` untimed steps, then exactly `steps` steps between two synchronisations.  HIP events on the
+        launch stream bracket every 8th of them (an event record costs stream time, so bracketing every step
+        would slow down the very steps being measured).  Returns (ms per step by the wall clock, average ms of a
+        bracketed step by the events)."""
         every = 8
-        jb.jd_profile_enable(op.handle, (args.steps + every - 1) // every, every)
-        torch.cuda.synchronize()
-        t_start = time.perf_counter()
-        for _ in range(args.steps):
-            op(q, kp, vp, bt, sl, out)
-        torch.cuda.synchronize()
-        t_end = time.perf_counter()
-        ms_sum, calls = jb.jd_profile_read(op.handle)
-        jb.jd_profile_enable(op.handle, 0, 1)
+        with torch.cuda.stream(stream):
+            for _ in range(warmup):
+                o(*t, out_, vector_kernels=vector)
+            torch.cuda.synchronize()
+            evs = []
+            t_start = time.perf_counter()
+            for i in range(steps):
+                if i % every == 0:
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    o(*t, out_, vector_kernels=vector)
+                    e1.record(stream)
+                    evs.append((e0, e1))
+                else:
+                    o(*t, out_, vector_kernels=vector)
+            torch.cuda.synchronize()
+            t_end = time.perf_counter()
+        kernel_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+        return (t_end - t_start) * 1e3 / steps, kernel_ms
+
+    def parity(got, ref):
+        d = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+        ma = float(d.max(initial=0.0))
+        mr = float((d / np.maximum(np.abs(ref.astype(np.float64)), 1e-3)).max(initial=0.0))
+        return {"max_abs": ma, "max_rel_floor1e-3": mr, "ok": bool(np.isfinite(got).all() and ma <= MAX_ABS and mr <= MAX_REL)}
+
+    def sampled_rows_parity(w, out_, nrows, seed):
+        """The oracle on `nrows` output rows (request, query head) drawn uniformly among the live requests."""
+        from oracle import jo
+        rng = np.random.default_rng(seed)
+        live = np.nonzero(w.seq_lens > 0)[0]
+        rows = np.stack([rng.choice(live, size=nrows), rng.integers(0, w.shape.num_q_heads, size=nrows)], axis=1)
+        ref = jo.decode_attention(w.q, w.k_pages, w.v_pages, w.block_table, w.seq_lens, rows=rows)
+        got = out_[torch.from_numpy(rows[:, 0]).to(dev), torch.from_numpy(rows[:, 1]).to(dev)].cpu().numpy()
+        r = parity(got, ref)
+        r["rows"] = int(nrows)
+        return r
+
+    t0 = time.time()
+    w = W.gen_config(args.cfg, args.seed, threads=threads)
+    s = w.shape
+    log(f"generated cfg{args.cfg} ({s.name}) T={w.total_tokens} KV={w.kv_bytes / 1e9:.3f} GB in {time.time() - t0:.1f}s")
+    q, kp, vp, bt, sl = upload(w)
+    out = torch.empty((s.batch, s.num_q_heads, s.head_dim), dtype=torch.float32, device=dev)
+    op = make_op(w, args.cu_budget)
+    ms_per_step, kernel_ms = timed_region(op, (q, kp, vp, bt, sl), out, args.steps, args.warmup, args.vector_kernels)
     # measured ceiling of a plain read sweep over the K pool (same stream, same process)
     sink = torch.zeros(1, dtype=torch.int32, device=dev)
     nbytes = kp.numel() * 2
@@ -112,31 +158,33 @@ def main() -> int:
         torch.cuda.synchronize()
     del dst
     op.check_flags()
-    # spread of single steps: an event pair around each of 100 more steps (the records add ~5 us of stream time
+    # spread of single steps: an event pair around each of 100 more steps (the records add a few us of stream time
     # to each interval, so these sit a little above the timed region's mean)
     with torch.cuda.stream(stream):
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(100)]
         for a, b in evs:
             a.record(stream)
-            op(q, kp, vp, bt, sl, out)
+            op(q, kp, vp, bt, sl, out, vector_kernels=args.vector_kernels)
             b.record(stream)
         torch.cuda.synchronize()
     single = np.sort(np.array([a.elapsed_time(b) * 1e3 for a, b in evs]))
-    ms_per_step = (t_end - t_start) * 1e3 / args.steps
     kv_bytes = w.kv_bytes
     tbs = kv_bytes / (ms_per_step * 1e-3) / 1e12
-    partial_ms = ms_sum[1] / max(calls, 1)
-    achieved = kv_bytes / (partial_ms * 1e-3) / 1e9 if partial_ms > 0 else 0.0
+    achieved = kv_bytes / (kernel_ms * 1e-3) / 1e9
 
+    # measured HBM bytes per launch come from profiler runs of this very command line; the file is keyed by
+    # everything that changes the launch, and a run it does not cover reports null
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not args.vector_kernels:
         try:
             with open(tpath) as f:
-                traffic = json.load(f).get(f"cfg{args.cfg}_variant{args.variant}")
+                traffic = json.load(f).get(f"cfg{args.cfg}_seed{args.seed}_cu{args.cu_budget}")
         except Exception:
             traffic = None
 
+    kernel_name = ("partition_kernel + partial_vector_kernel + combine_kernel" if args.vector_kernels
+                   else "decode_fused_kernel (partition + split-KV partial attention + combine)")
     result = {
         "metric": "decode_attention_kv_bandwidth",
         "value": round(tbs, 4),
@@ -160,13 +208,11 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"cfg{args.cfg} {s.name}: batch {s.batch}, {s.num_q_heads}q/{s.num_kv_heads}kv heads, "
                                f"head_dim {s.head_dim}, page 16, seed {args.seed}, T={w.total_tokens} tokens",
-                   "kv_bytes_per_step": kv_bytes, "variant": args.variant, "cu_budget": args.cu_budget,
+                   "kv_bytes_per_step": kv_bytes, "cu_budget": args.cu_budget, "vector_kernels": args.vector_kernels,
                    "derived_us_per_model_step": round(ms_per_step * 1e3 * s.layers, 1), "layers": s.layers},
-        "kernel_ms": {"partition": round(ms_sum[0] / max(calls, 1), 5), "partial": round(partial_ms, 5),
-                      "combine": round(ms_sum[2] / max(calls, 1), 5)},
-        "roofline": {"bound": "hbm", "kernel": "decode_fused_kernel (partition + split-KV partial attention + combine)" if args.variant != 1 else "partial_vector_kernel", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": traffic},
+                     "kernel_us": round(kernel_ms * 1e3, 2), "traffic": traffic},
     }
 
     def time_steps(o, lens_t, steps=60, warm=10):
@@ -180,14 +226,70 @@ def main() -> int:
             torch.cuda.synchronize()
             return (time.perf_counter() - t0_) * 1e6 / steps
 
+    def merged_workload(n):
+        # long-tail migration aggregates the stragglers of n DP workers on one target (Sub-stage Merging):
+        # n independent straggler draws (cfg3, seeds seed .. seed + n - 1) merged into one batch
+        s3 = W.SHAPES[3]
+        lens_m = np.concatenate([W.draw_seq_lens(3, np.random.default_rng(args.seed + i)) for i in range(n)])
+        return W.build(dataclasses.replace(s3, batch=len(lens_m)), lens_m, seed=args.seed, cfg=30 + n, threads=threads)
+
+    def prefill_case(shape, name, lens_p, ql_p, reps=10, parity_tokens=0):
+        """Time jd_prefill_attention on `shape` for context+new lengths lens_p of which the last ql_p are new."""
+        nreq = len(lens_p)
+        wp = W.build(dataclasses.replace(shape, batch=nreq), lens_p.astype(np.int32), seed=args.seed + 1, cfg=70,
+                     threads=threads)
+        offs = np.concatenate([[0], np.cumsum(ql_p)[:-1]]).astype(np.int32)
+        tq = int(ql_p.sum())
+        q_host = W.f32_to_bf16_bits(np.random.default_rng(args.seed + 2).standard_normal(
+            (tq, shape.num_q_heads, shape.head_dim), dtype=np.float32))
+        qp = torch.from_numpy(q_host.view(np.int16)).to(dev).view(torch.bfloat16)
+        _, kpp, vpp, btp, slp = upload(wp)
+        qlp = torch.from_numpy(ql_p.astype(np.int32)).to(dev)
+        ofp = torch.from_numpy(offs).to(dev)
+        outp = torch.empty((tq, shape.num_q_heads, shape.head_dim), dtype=torch.float32, device=dev)
+        o2 = make_op(wp)
+        with torch.cuda.stream(stream):
+            for _ in range(2):
+                o2.prefill(qp, kpp, vpp, btp, slp, qlp, ofp, int(ql_p.max()), out=outp)
+            e0_, e1_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0_.record(stream)
+            for _ in range(reps):
+                o2.prefill(qp, kpp, vpp, btp, slp, qlp, ofp, int(ql_p.max()), out=outp)
+            e1_.record(stream)
+            torch.cuda.synchronize()
+        o2.check_flags()
+        o2.close()
+        ms = e0_.elapsed_time(e1_) / reps
+        ctx = lens_p - ql_p
+        pairs = int((ql_p * ctx + ql_p * (ql_p + 1) // 2).sum())      # (query, key) pairs under the causal mask
+        flops = 4.0 * shape.num_q_heads * shape.head_dim * pairs
+        row = {"case": name, "requests": nreq, "new_tokens": tq, "kv_tokens": int(lens_p.sum()),
+               "ms": round(ms, 4), "new_tokens_per_s": round(tq / ms * 1e3, 1),
+               "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": round(flops / ms / 1e9, 2),
+                            "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                            "frac": round(flops / ms / 1e9 / MFMA_PEAK_TFLOPS, 4), "traffic": None}}
+        if parity_tokens:
+            # new token t of request b is the decode step of its first ctx + t + 1 tokens: the oracle on sampled tokens
+            from oracle import jo
+            rng = np.random.default_rng(args.seed + 3)
+            sb = rng.integers(0, nreq, size=parity_tokens)
+            st = np.array([rng.integers(0, ql_p[b]) for b in sb])
+            st[: min(nreq, parity_tokens)] = (ql_p[sb[: min(nreq, parity_tokens)]] - 1)     # last tokens: the whole cache
+            rows = offs[sb] + st
+            ref = jo.decode_attention(np.ascontiguousarray(q_host[rows]), wp.k_pages, wp.v_pages,
+                                      np.ascontiguousarray(wp.block_table[sb]), (ctx[sb] + st + 1).astype(np.int32))
+            r = parity(outp[torch.from_numpy(rows).to(dev)].cpu().numpy(), ref)
+            r["tokens"] = int(parity_tokens)
+            row["parity_on_sample"] = r
+        return row
+
     if args.sweep == "cu":
         # the paper bounds the SMs a sub-stage may use and finds small-batch rollout insensitive to them
         # (Sub-stage Multiplexing, "Compute Resource Utilization"); the same experiment with the library's CU budget
         cus = torch.cuda.get_device_properties(0).multi_processor_count
         rows = []
         for pct in (25, 50, 75, 100):
-            o2 = jb.DecodeAttention(s.batch, s.num_q_heads, s.num_kv_heads, s.head_dim, w.max_pages_per_seq,
-                                    w.num_pages, variant=args.variant, cu_budget=cus * pct // 100)
+            o2 = make_op(w, cus * pct // 100)
             us = time_steps(o2, sl)
             o2.close()
             rows.append({"cu_pct": pct, "cu_budget": cus * pct // 100, "us_per_step": round(us, 2),
@@ -214,35 +316,19 @@ def main() -> int:
             torch.cuda.synchronize()
 
     if args.sweep == "merge":
-        # long-tail migration aggregates the stragglers of n DP workers on one target (Sub-stage Merging):
-        # n independent cfg3 draws merged into one batch; a bandwidth-bound kernel should charge the sum of the bytes
-        s3 = W.SHAPES[3]
         rows = []
         for n in (1, 2, 4, 8):
-            lens_m = np.concatenate([W.draw_seq_lens(3, np.random.default_rng(args.seed + i)) for i in range(n)])
-            wm = W.build(dataclasses.replace(s3, batch=len(lens_m)), lens_m, seed=args.seed, cfg=30 + n,
-                         threads=min(16, os.cpu_count() or 8))
-            qm = torch.from_numpy(wm.q.view(np.int16)).to(dev).view(torch.bfloat16)
-            km = torch.from_numpy(wm.k_pages.view(np.int16)).to(dev).view(torch.bfloat16)
-            vm = torch.from_numpy(wm.v_pages.view(np.int16)).to(dev).view(torch.bfloat16)
-            btm = torch.from_numpy(wm.block_table).to(dev)
-            slm = torch.from_numpy(wm.seq_lens).to(dev)
-            om = torch.empty((len(lens_m), s3.num_q_heads, s3.head_dim), dtype=torch.float32, device=dev)
-            o2 = jb.DecodeAttention(len(lens_m), s3.num_q_heads, s3.num_kv_heads, s3.head_dim, wm.max_pages_per_seq,
-                                    wm.num_pages, variant=args.variant)
-            with torch.cuda.stream(stream):
-                for _ in range(10):
-                    o2(qm, km, vm, btm, slm, om)
-                torch.cuda.synchronize()
-                t0_ = time.perf_counter()
-                for _ in range(100):
-                    o2(qm, km, vm, btm, slm, om)
-                torch.cuda.synchronize()
-                us = (time.perf_counter() - t0_) * 1e6 / 100
+            wm = merged_workload(n)
+            tm = upload(wm)
+            om = torch.empty((wm.shape.batch, wm.shape.num_q_heads, wm.shape.head_dim), dtype=torch.float32, device=dev)
+            o2 = make_op(wm)
+            ms_m, _ = timed_region(o2, tm, om, 100, 10)
+            o2.check_flags()
             o2.close()
-            rows.append({"workers_merged": n, "requests": len(lens_m), "tokens": wm.total_tokens,
-                         "us_per_step": round(us, 2), "kv_tb_per_s": round(wm.kv_bytes / us / 1e6, 4)})
-            del qm, km, vm, om
+            rows.append({"workers_merged": n, "requests": wm.shape.batch, "tokens": wm.total_tokens,
+                         "us_per_step": round(ms_m * 1e3, 2), "kv_tb_per_s": round(wm.kv_bytes / ms_m / 1e9, 4),
+                         "parity_on_sample": sampled_rows_parity(wm, om, 128, args.seed + n)})
+            del tm, om
         for r in rows:
             r["us_vs_n_times_single"] = round(r["us_per_step"] / (rows[0]["us_per_step"] * r["workers_merged"]), 3)
         result["merged_straggler_sweep"] = rows
@@ -297,48 +383,11 @@ def main() -> int:
     if args.sweep == "prefill":
         # KV recomputation after a migration and the prefill of a new turn (Sub-stage Merging; Motivation,
         # "Multi-turn Rollout Idling"), on this config's head shape and length distribution
-        MFMA_PEAK_TFLOPS = 2500.0   # dense bf16
-        rows = []
         nreq = min(32, s.batch)
         base = w.seq_lens[:nreq].astype(np.int64)
-        for name, lens_p, ql_p in (("recompute_whole_request", base, base),
-                                    ("new_turn_512_after_context", base + 512, np.full(nreq, 512, dtype=np.int64))):
-            wp = W.build(dataclasses.replace(s, batch=nreq), lens_p.astype(np.int32), seed=args.seed + 1, cfg=70,
-                         threads=min(16, os.cpu_count() or 8))
-            offs = np.concatenate([[0], np.cumsum(ql_p)[:-1]]).astype(np.int32)
-            tq = int(ql_p.sum())
-            qp = torch.randn((tq, s.num_q_heads, s.head_dim), device=dev).bfloat16()
-            kpp = torch.from_numpy(wp.k_pages.view(np.int16)).to(dev).view(torch.bfloat16)
-            vpp = torch.from_numpy(wp.v_pages.view(np.int16)).to(dev).view(torch.bfloat16)
-            btp = torch.from_numpy(wp.block_table).to(dev)
-            slp = torch.from_numpy(wp.seq_lens).to(dev)
-            qlp = torch.from_numpy(ql_p.astype(np.int32)).to(dev)
-            ofp = torch.from_numpy(offs).to(dev)
-            outp = torch.empty((tq, s.num_q_heads, s.head_dim), dtype=torch.float32, device=dev)
-            o2 = jb.DecodeAttention(nreq, s.num_q_heads, s.num_kv_heads, s.head_dim, wp.max_pages_per_seq, wp.num_pages)
-            reps = 10
-            with torch.cuda.stream(stream):
-                for _ in range(2):
-                    o2.prefill(qp, kpp, vpp, btp, slp, qlp, ofp, int(ql_p.max()), out=outp)
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record(stream)
-                for _ in range(reps):
-                    o2.prefill(qp, kpp, vpp, btp, slp, qlp, ofp, int(ql_p.max()), out=outp)
-                e1.record(stream)
-                torch.cuda.synchronize()
-            o2.check_flags()
-            o2.close()
-            ms = e0.elapsed_time(e1) / reps
-            ctx = lens_p - ql_p
-            pairs = int((ql_p * ctx + ql_p * (ql_p + 1) // 2).sum())      # (query, key) pairs under the causal mask
-            flops = 4.0 * s.num_q_heads * s.head_dim * pairs
-            rows.append({"case": name, "requests": nreq, "new_tokens": tq, "kv_tokens": int(lens_p.sum()),
-                         "ms": round(ms, 4), "new_tokens_per_s": round(tq / ms * 1e3, 1),
-                         "roofline": {"bound": "mfma", "achieved": round(flops / ms / 1e9, 2), "peak": MFMA_PEAK_TFLOPS,
-                                      "unit": "TFLOP/s", "frac": round(flops / ms / 1e9 / MFMA_PEAK_TFLOPS, 4),
-                                      "traffic": None}})
-            del kpp, vpp, qp, outp
-        result["prefill_sweep"] = rows
+        result["prefill_sweep"] = [
+            prefill_case(s, "recompute_whole_request", base, base, parity_tokens=96),
+            prefill_case(s, "new_turn_512_after_context", base + 512, np.full(nreq, 512, dtype=np.int64), parity_tokens=96)]
 
     if not args.no_cpu_baseline:
         from oracle import jo
@@ -362,9 +411,6 @@ def main() -> int:
             passes += 1
         dt /= passes
         got = out[torch.tensor(rows, device=dev)].cpu().numpy()
-        diff = np.abs(got.astype(np.float64) - ref.astype(np.float64))
-        max_abs = float(diff.max())
-        max_rel = float((diff / np.maximum(np.abs(ref.astype(np.float64)), 1e-3)).max())
         result["cpu_baseline"] = {"value": round(sub.kv_bytes / dt / 1e12, 6), "unit": "TB/s", "cores": cores,
                                   "kind": "oracle",
                                   "sample": f"first {len(rows)} of {s.batch} requests ({sub.total_tokens} tokens, "
@@ -385,9 +431,51 @@ def main() -> int:
         result["cpu_baseline"]["one_core"] = {"value": round(sub1.kv_bytes / dt1 / 1e12, 6), "unit": "TB/s",
                                               "sample": f"first {len(rows1)} requests ({sub1.total_tokens} tokens), "
                                                         f"{dt1:.2f}s wall"}
-        result["parity_on_sample"] = {"max_abs": max_abs, "max_rel_floor1e-3": max_rel,
-                                      "ok": bool(max_abs <= 5e-3 and max_rel <= 1e-2)}
+        result["parity_on_sample"] = parity(got, ref)
     op.close()
+
+    # ---- the other timed configurations, the merged-straggler batch and the prefill of a new turn ----
+    if args.cfg == 2 and not args.headline_only and not args.vector_kernels and args.sweep == "none":
+        shape2 = s
+        base2 = w.seq_lens[:32].astype(np.int64)
+        del q, kp, vp, bt, sl, out, w
+        torch.cuda.empty_cache()
+        extra = []
+
+        def decode_entry(name, wx, parity_seed):
+            tx = upload(wx)
+            ox = torch.empty((wx.shape.batch, wx.shape.num_q_heads, wx.shape.head_dim), dtype=torch.float32, device=dev)
+            o2 = make_op(wx)
+            ms_x, kms_x = timed_region(o2, tx, ox, 100, 20)
+            o2.check_flags()
+            o2.close()
+            ach = wx.kv_bytes / (kms_x * 1e-3) / 1e9
+            e = {"workload": name, "tokens": wx.total_tokens, "kv_bytes_per_step": wx.kv_bytes, "steps": 100, "warmup": 20,
+                 "us_per_step": round(ms_x * 1e3, 2), "kv_tb_per_s": round(wx.kv_bytes / ms_x / 1e9, 4),
+                 "pct_of_hbm_peak": round(100.0 * wx.kv_bytes / ms_x / 1e6 / HBM_PEAK_GBS, 2),
+                 "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": round(ach / HBM_PEAK_GBS, 4), "kernel_us": round(kms_x * 1e3, 2)},
+                 "parity_on_sample": sampled_rows_parity(wx, ox, 256, parity_seed)}
+            log(f"{name}: {e['us_per_step']} us/step, frac {e['roofline']['frac']}, parity ok={e['parity_on_sample']['ok']}")
+            return e
+
+        for cfg in (3, 4, 5):
+            t0 = time.time()
+            wx = W.gen_config(cfg, args.seed, threads=threads)
+            sx = wx.shape
+            extra.append(decode_entry(f"cfg{cfg} {sx.name}: batch {sx.batch}, {sx.num_q_heads}q/{sx.num_kv_heads}kv heads, "
+                                      f"head_dim {sx.head_dim}, seed {args.seed}", wx, 100 + cfg))
+            del wx
+        wm = merged_workload(8)
+        extra.append(decode_entry(f"merged stragglers: 8 straggler draws (cfg3 seeds {args.seed}..{args.seed + 7}) in one "
+                                  f"batch of {wm.shape.batch}", wm, 108))
+        del wm
+        pe = prefill_case(shape2, "prefill of a 512-token turn after the context, first 32 requests of the cfg2 draw",
+                          base2 + 512, np.full(32, 512, dtype=np.int64), parity_tokens=96)
+        pe["workload"] = pe.pop("case")
+        log(f"prefill: {pe['ms']} ms, frac {pe['roofline']['frac']}, parity ok={pe['parity_on_sample']['ok']}")
+        extra.append(pe)
+        result["configs"] = extra
     print(json.dumps(result))
     return 0
 

@@ -40,21 +40,14 @@ typedef struct jd_handle jd_handle;
 typedef enum {
     JD_OK = 0,
     JD_ERR_INVALID_ARG = 1, /* null pointer, misaligned buffer, non-positive size, heads not divisible */
-    JD_ERR_UNSUPPORTED = 2, /* head_dim not in {64,128}, page_size != 16, group size > 16, unknown variant */
+    JD_ERR_UNSUPPORTED = 2, /* head_dim not in {64,128}, page_size != 16, group size > 16, batch > 8192 */
     JD_ERR_HIP = 3,         /* a HIP runtime call or kernel launch failed */
-    JD_ERR_BAD_INPUT = 4    /* device-side check: a page id or sequence length outside the declared bounds */
+    JD_ERR_BAD_INPUT = 4    /* device-side check: a page id, sequence length or query offset outside the declared bounds */
 } jd_status;
 
-/* Kernel family used for the split-KV partial pass. */
-typedef enum {
-    JD_VARIANT_DEFAULT = 0, /* the library's choice (the fastest measured for the shape) */
-    JD_VARIANT_VECTOR = 1,  /* vector ALU: dot2 products, DPP/shuffle reductions, pages read straight to registers */
-    JD_VARIANT_MFMA = 2     /* GQA group packed into a matrix-core tile, pages staged in LDS by direct loads;
-                               partition, partial pass and combine fused into one launch */
-} jd_variant;
-
 typedef struct {
-    int32_t batch;             /* B: rows of q/out/block_table/seq_lens; requests with seq_len 0 are skipped */
+    int32_t batch;             /* B: rows of q/out/block_table/seq_lens, at most 8192 (the work partition keeps its
+                                  tables in LDS; more is JD_ERR_UNSUPPORTED); requests with seq_len 0 are skipped */
     int32_t num_q_heads;       /* Hq */
     int32_t num_kv_heads;      /* Hkv; must divide Hq; query head h reads kv head h / (Hq / Hkv) */
     int32_t head_dim;          /* D: 64 or 128 */
@@ -62,10 +55,9 @@ typedef struct {
     int32_t max_pages_per_seq; /* MAXP: row stride (in entries) of block_table */
     int32_t num_pages;         /* NP: pages in k_pages / v_pages; page ids are checked against it */
     float softmax_scale;       /* 0 means 1 / sqrt(D) */
-    int32_t variant;           /* a jd_variant */
-    int32_t cu_budget;         /* 0: the library's choice (all compute units; three quarters of them for the
-                                  matrix-core variant with head_dim 128, where that already saturates HBM);
-                                  otherwise the number of workgroup slots the partial pass may occupy (spatial
+    int32_t cu_budget;         /* 0: the library's choice (all compute units; three quarters of them with
+                                  head_dim 128, where that already saturates HBM); otherwise the number of
+                                  one-per-compute-unit workgroups the decode kernel is launched with (spatial
                                   sharing with a co-located job; Sub-stage Multiplexing, "Dynamic Resource
                                   Allocation") */
 } jd_config;
@@ -106,7 +98,8 @@ jd_status jd_create(const jd_config *cfg, jd_handle **out);
  * influence the result, whatever bits they hold.  The call only enqueues work (work partition,
  * split-KV partial pass, log-sum-exp combine) on `stream`; it performs no allocation, no host
  * synchronisation and no device-to-host copy, so it may be captured into a HIP graph.  Calls on
- * one handle share its workspace: they must be ordered on one stream (or otherwise serialised).
+ * one handle share its workspace: they must be ordered on one stream (or otherwise serialised), and
+ * seq_lens must not change while a call that reads it is running.
  * Page ids outside [0, NP) and lengths beyond 16*MAXP are never dereferenced: the offending page is
  * replaced by page 0 / the length clamped (the affected rows are then meaningless) and a sticky flag
  * is raised that jd_check_device_flags reports.
@@ -147,6 +140,9 @@ jd_status jd_append_kv(jd_handle *h, const void *k_new, const void *v_new, void 
  *   q_lens      int32 [B]                  device, read; 0 = nothing to do for the request; values above L
  *                                          are clamped to L
  *   q_offsets   int32 [B]                  device, read; the rows of different requests must not overlap
+ *   total_q_rows  host value: TQ, the rows q and out hold.  A request whose rows q_offsets[b] .. q_offsets[b]+n-1
+ *                                          do not lie inside [0, TQ) is skipped (nothing of it is read or written)
+ *                                          and raises the sticky flag reported by jd_check_device_flags
  *   max_q_len   host value: an upper bound of q_lens (it sizes the launch; tokens beyond it are not computed)
  *   out         fp32 [TQ, Hq, D]           device, 16-byte aligned; the rows of the new tokens are written,
  *                                          all others are left untouched
@@ -157,63 +153,17 @@ jd_status jd_append_kv(jd_handle *h, const void *k_new, const void *v_new, void 
  */
 jd_status jd_prefill_attention(jd_handle *h, const void *q, const void *k_pages, const void *v_pages,
                                const int32_t *block_table, const int32_t *seq_lens, const int32_t *q_lens,
-                               const int32_t *q_offsets, int32_t max_q_len, float *out, void *stream);
+                               const int32_t *q_offsets, int32_t total_q_rows, int32_t max_q_len, float *out,
+                               void *stream);
 
 /*
  * Synchronise `stream` and report device-side input checks of the calls completed so far:
- * JD_OK, JD_ERR_BAD_INPUT (and clears the flag) or JD_ERR_HIP.
+ * JD_OK, JD_ERR_BAD_INPUT (and clears the flag) or JD_ERR_HIP.  The message names what was seen: a
+ * sequence length beyond 16*MAXP (clamped), a page id outside [0, NP) (page 0 read or the append
+ * skipped), seq_lens changed while a decode kernel was running (rows meaningless), prefill rows
+ * outside [0, TQ) (request skipped).
  */
 jd_status jd_check_device_flags(jd_handle *h, void *stream);
-
-/*
- * Run only the work partitioner for seq_lens (device, int32 [B]) and copy its tables to the
- * host (synchronises `stream`).  For tests and tuning.  Waves work in groups of `group_waves`
- * (1 for the vector variant): member i of a group serves the kv heads i, i + group_waves, ...; the
- * work of a step is the line of group-units (request, kv-head group, page), request-major, then
- * kv-head group, then page, and a group of waves owns one span of it.
- *   header_host      int32 [8]: {units, span, active_groups, wave_slots, group_waves, 0, 0, 0}
- *                    units = sum over requests of ceil(L/16) * Hkv / group_waves;
- *                    group g < active_groups owns units [g*span, min((g+1)*span, units)) and consists of
- *                    waves g*group_waves .. (g+1)*group_waves - 1
- *   wave_start_host  int32 [wave_slots * 4]: {request, kv_head, page, 0} of the first page each wave of an
- *                    active group works on (zeros for the others)
- *   cum_pages_host   int32 [B + 1]: pages of all requests before b (exclusive prefix of ceil(L/16))
- * Any of the three host pointers may be NULL.
- */
-jd_status jd_debug_partition(jd_handle *h, const int32_t *seq_lens, int32_t *header_host,
-                             int32_t *wave_start_host, int32_t *cum_pages_host, void *stream);
-
-/*
- * The schedule for a work line of `units` page-units and `wave_slots` waves, as the kernels compute
- * it: out = {span, active_waves} (see jd_debug_partition).  Pure host function.
- */
-jd_status jd_debug_schedule(int32_t units, int32_t wave_slots, int32_t out[2]);
-
-/*
- * Per-kernel timing with HIP events, for benchmarks.  jd_profile_enable creates 4 * max_calls
- * events (max_calls = 0 frees them and switches timing off); while enabled, every `every`-th
- * jd_decode_attention call (the first one included), up to max_calls of them, records an event
- * before and after each of its three kernels on the call's stream (do not capture such calls into
- * a graph; an event record costs a few microseconds of stream time, hence the sampling).
- * jd_profile_read synchronises on the last recorded event, stores the summed durations in
- * milliseconds of {work partition, split-KV partial pass, combine} and the number of calls summed,
- * and restarts the recording window.  The matrix-core variant runs all three phases in one fused
- * kernel: its whole duration is reported under the partial pass, the other two read 0.
- */
-jd_status jd_profile_enable(jd_handle *h, int32_t max_calls, int32_t every);
-jd_status jd_profile_read(jd_handle *h, float ms_sum[3], int32_t *calls);
-
-/*
- * Plain streaming kernels of known HBM traffic, for benchmarks and for scaling profiler byte
- * counters: a read-only sweep of `bytes` bytes at src (sink: 4 writable device bytes, practically
- * never written) and a copy of `bytes` bytes.  Device pointers, 16-byte aligned; bytes is rounded
- * down to a multiple of 16.  They only enqueue on `stream`.
- */
-jd_status jd_debug_stream_read(const void *src, size_t bytes, void *sink, void *stream);
-jd_status jd_debug_stream_copy(void *dst, const void *src, size_t bytes, void *stream);
-
-/* Number of wave slots the partial pass of this handle is launched with (grid waves). */
-int32_t jd_wave_slots(const jd_handle *h);
 
 /* Free the workspace and the handle.  NULL is accepted. */
 jd_status jd_destroy(jd_handle *h);

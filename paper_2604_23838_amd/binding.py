@@ -10,25 +10,22 @@ import ctypes as C
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# JIGSAW_DECODE_LIB points tuning runs at an alternative build of the same library
-LIB_PATH = os.environ.get("JIGSAW_DECODE_LIB") or os.path.join(_HERE, "libjigsaw_decode.so")
+LIB_PATH = os.path.join(_HERE, "libjigsaw_decode.so")
 
 JD_OK, JD_ERR_INVALID_ARG, JD_ERR_UNSUPPORTED, JD_ERR_HIP, JD_ERR_BAD_INPUT = range(5)
-JD_VARIANT_DEFAULT, JD_VARIANT_VECTOR, JD_VARIANT_MFMA = range(3)
 
+# the product ABI (include/jigsaw_decode.h) and the inspection / measurement calls (include/jigsaw_decode_bench.h)
 EXPORTS = ("jd_validate_config", "jd_workspace_bytes", "jd_create", "jd_decode_attention", "jd_append_kv",
-           "jd_prefill_attention",
-           "jd_check_device_flags", "jd_debug_partition", "jd_profile_enable", "jd_profile_read",
-           "jd_debug_stream_read", "jd_debug_stream_copy",
-           "jd_debug_schedule", "jd_wave_slots", "jd_destroy",
-           "jd_last_error_string")
+           "jd_prefill_attention", "jd_check_device_flags", "jd_destroy", "jd_last_error_string")
+BENCH_EXPORTS = ("jd_debug_partition", "jd_debug_schedule", "jd_wave_slots", "jd_debug_stream_read",
+                 "jd_debug_stream_copy", "jd_bench_decode_attention_vector", "jd_bench_stream_create_cu_masked",
+                 "jd_bench_stream_destroy")
 
 
 class jd_config(C.Structure):
     _fields_ = [("batch", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("page_size", C.c_int32), ("max_pages_per_seq", C.c_int32),
-                ("num_pages", C.c_int32), ("softmax_scale", C.c_float), ("variant", C.c_int32),
-                ("cu_budget", C.c_int32)]
+                ("num_pages", C.c_int32), ("softmax_scale", C.c_float), ("cu_budget", C.c_int32)]
 
 
 class JdError(RuntimeError):
@@ -66,16 +63,18 @@ def lib():
         l.jd_decode_attention.restype = C.c_int
         l.jd_append_kv.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
         l.jd_append_kv.restype = C.c_int
-        l.jd_prefill_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_int32, vp, vp]
+        l.jd_prefill_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_int32, C.c_int32, vp, vp]
         l.jd_prefill_attention.restype = C.c_int
         l.jd_check_device_flags.argtypes = [vp, vp]
         l.jd_check_device_flags.restype = C.c_int
         l.jd_debug_partition.argtypes = [vp, vp, vp, vp, vp, vp]
         l.jd_debug_partition.restype = C.c_int
-        l.jd_profile_enable.argtypes = [vp, C.c_int32, C.c_int32]
-        l.jd_profile_enable.restype = C.c_int
-        l.jd_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
-        l.jd_profile_read.restype = C.c_int
+        l.jd_bench_decode_attention_vector.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
+        l.jd_bench_decode_attention_vector.restype = C.c_int
+        l.jd_bench_stream_create_cu_masked.argtypes = [C.c_int32, C.POINTER(vp)]
+        l.jd_bench_stream_create_cu_masked.restype = C.c_int
+        l.jd_bench_stream_destroy.argtypes = [vp]
+        l.jd_bench_stream_destroy.restype = C.c_int
         l.jd_debug_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
         l.jd_debug_stream_read.restype = C.c_int
         l.jd_debug_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
@@ -126,11 +125,11 @@ def jd_append_kv(handle, k_new, v_new, k_pages, v_pages, block_table, seq_lens, 
         raise JdError(st, jd_last_error_string(handle))
 
 
-def jd_prefill_attention(handle, q, k_pages, v_pages, block_table, seq_lens, q_lens, q_offsets, max_q_len, out,
-                         stream=0) -> None:
-    """Device addresses (ints); max_q_len is a host integer."""
+def jd_prefill_attention(handle, q, k_pages, v_pages, block_table, seq_lens, q_lens, q_offsets, total_q_rows,
+                         max_q_len, out, stream=0) -> None:
+    """Device addresses (ints); total_q_rows and max_q_len are host integers."""
     st = lib().jd_prefill_attention(handle, q, k_pages, v_pages, block_table, seq_lens, q_lens, q_offsets,
-                                    int(max_q_len), out, stream)
+                                    int(total_q_rows), int(max_q_len), out, stream)
     if st != JD_OK:
         raise JdError(st, jd_last_error_string(handle))
 
@@ -168,20 +167,26 @@ def jd_debug_partition(handle, seq_lens, batch: int, stream=0):
     return list(hdr), [w[4 * i:4 * i + 4] for i in range(slots)], list(cum)
 
 
-def jd_profile_enable(handle, max_calls: int, every: int = 1) -> None:
-    st = lib().jd_profile_enable(handle, max_calls, every)
+def jd_bench_decode_attention_vector(handle, q, k_pages, v_pages, block_table, seq_lens, out, stream=0) -> None:
+    """The decode step by the vector-ALU comparison kernels; arguments as for jd_decode_attention."""
+    st = lib().jd_bench_decode_attention_vector(handle, q, k_pages, v_pages, block_table, seq_lens, out, stream)
     if st != JD_OK:
         raise JdError(st, jd_last_error_string(handle))
 
 
-def jd_profile_read(handle):
-    """Returns ([ms_partition, ms_partial, ms_combine] summed over the recorded calls, calls)."""
-    ms = (C.c_float * 3)()
-    n = C.c_int32()
-    st = lib().jd_profile_read(handle, ms, C.byref(n))
+def jd_bench_stream_create_cu_masked(num_cus: int) -> int:
+    """A hipStream_t (as an int) confined to `num_cus` compute units."""
+    h = C.c_void_p()
+    st = lib().jd_bench_stream_create_cu_masked(num_cus, C.byref(h))
     if st != JD_OK:
-        raise JdError(st, jd_last_error_string(handle))
-    return [float(x) for x in ms], int(n.value)
+        raise JdError(st, f"no stream confined to {num_cus} compute units")
+    return int(h.value)
+
+
+def jd_bench_stream_destroy(stream: int) -> None:
+    st = lib().jd_bench_stream_destroy(stream)
+    if st != JD_OK:
+        raise JdError(st, "jd_bench_stream_destroy failed")
 
 
 def jd_debug_stream_read(src, nbytes: int, sink, stream=0) -> None:
@@ -211,9 +216,9 @@ class DecodeAttention:
     """
 
     def __init__(self, batch, num_q_heads, num_kv_heads, head_dim, max_pages_per_seq, num_pages, *,
-                 page_size=16, softmax_scale=0.0, variant=JD_VARIANT_DEFAULT, cu_budget=0):
+                 page_size=16, softmax_scale=0.0, cu_budget=0):
         self.cfg = jd_config(batch, num_q_heads, num_kv_heads, head_dim, page_size, max_pages_per_seq,
-                             num_pages, softmax_scale, variant, cu_budget)
+                             num_pages, softmax_scale, cu_budget)
         self.handle = jd_create(self.cfg)
 
     def _check(self, q, k_pages, v_pages, block_table, seq_lens, out):
@@ -229,15 +234,17 @@ class DecodeAttention:
             if not (t.is_cuda and t.dtype == dt and tuple(t.shape) == shape and t.is_contiguous()):
                 raise ValueError(f"expected contiguous CUDA {dt} tensor of shape {shape}, got {t.dtype} {tuple(t.shape)}")
 
-    def __call__(self, q, k_pages, v_pages, block_table, seq_lens, out=None, stream=None):
+    def __call__(self, q, k_pages, v_pages, block_table, seq_lens, out=None, stream=None, *, vector_kernels=False):
+        """One decode step.  vector_kernels=True runs the vector-ALU comparison kernels instead (benchmarks, tests)."""
         import torch
         if out is None:
             out = torch.empty((self.cfg.batch, self.cfg.num_q_heads, self.cfg.head_dim),
                               dtype=torch.float32, device=q.device)
         self._check(q, k_pages, v_pages, block_table, seq_lens, out)
         s = torch.cuda.current_stream() if stream is None else stream
-        jd_decode_attention(self.handle, q.data_ptr(), k_pages.data_ptr(), v_pages.data_ptr(),
-                            block_table.data_ptr(), seq_lens.data_ptr(), out.data_ptr(), s.cuda_stream)
+        call = jd_bench_decode_attention_vector if vector_kernels else jd_decode_attention
+        call(self.handle, q.data_ptr(), k_pages.data_ptr(), v_pages.data_ptr(),
+             block_table.data_ptr(), seq_lens.data_ptr(), out.data_ptr(), s.cuda_stream)
         return out
 
     def append(self, k_new, v_new, k_pages, v_pages, block_table, seq_lens, active=None, stream=None):
@@ -271,8 +278,8 @@ class DecodeAttention:
             raise ValueError("out must be a contiguous CUDA float32 tensor shaped like q")
         s = torch.cuda.current_stream() if stream is None else stream
         jd_prefill_attention(self.handle, q.data_ptr(), k_pages.data_ptr(), v_pages.data_ptr(), block_table.data_ptr(),
-                             seq_lens.data_ptr(), q_lens.data_ptr(), q_offsets.data_ptr(), max_q_len, out.data_ptr(),
-                             s.cuda_stream)
+                             seq_lens.data_ptr(), q_lens.data_ptr(), q_offsets.data_ptr(), q.shape[0], max_q_len,
+                             out.data_ptr(), s.cuda_stream)
         return out
 
     def check_flags(self, stream=None):

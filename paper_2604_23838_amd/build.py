@@ -26,13 +26,13 @@ def _hipcc() -> str:
     return "hipcc"
 
 
-def build(verbose: bool = False, defines: tuple = (), lib: str = LIB, obj_dir: str = OBJ_DIR) -> str:
-    os.makedirs(obj_dir, exist_ok=True)
+def build(verbose: bool = False) -> str:
+    os.makedirs(OBJ_DIR, exist_ok=True)
     hipcc = _hipcc()
 
     def compile_one(src: str) -> str:
-        obj = os.path.join(obj_dir, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, *[f"-D{d}" for d in defines], "-c", os.path.join(CSRC, src), "-o", obj]
+        obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
+        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         err = "\n".join(l for l in r.stderr.splitlines() if "not a recognized feature" not in l)
         if r.returncode != 0:
@@ -43,11 +43,11 @@ def build(verbose: bool = False, defines: tuple = (), lib: str = LIB, obj_dir: s
 
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs],
+    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs],
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr}")
-    return lib
+    return LIB
 
 
 if __name__ == "__main__":

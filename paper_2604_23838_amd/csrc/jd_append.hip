@@ -23,12 +23,12 @@ __global__ __launch_bounds__(kThreads) void append_kv_kernel(Params p, const uin
     if (!on || L < 0) return;
     const int pg = L / kPage, slot = L % kPage;
     if (pg >= p.maxp) {
-        if (threadIdx.x == 0) atomicOr(&p.header[kHdrBadInput], 1);
+        if (threadIdx.x == 0) atomicOr(&p.header[kHdrBadInput], kBadLength);
         return;
     }
     const int id = p.block_table[static_cast<size_t>(b) * p.maxp + pg];
     if (static_cast<unsigned>(id) >= static_cast<unsigned>(p.NP)) {
-        if (threadIdx.x == 0) atomicOr(&p.header[kHdrBadInput], 2);
+        if (threadIdx.x == 0) atomicOr(&p.header[kHdrBadInput], kBadPage);
         return;
     }
     const int chunks_per_row = p.D / 8;  // 16-byte chunks of one token row

@@ -48,26 +48,10 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) char lds_char;
 
-#ifndef JD_MFMA_WAVES
-#define JD_MFMA_WAVES 4
-#endif
-constexpr int kWaves = JD_MFMA_WAVES;  // waves per block; one block per compute unit (LDS-limited)
+constexpr int kWaves = 4;  // waves per block; one block per compute unit (LDS-limited)
 constexpr int kLdsBudget = 160 * 1024;
-
-#ifdef JD_TIMING
-// Development aid (not built by default): per-wave phase time stamps of the constant 100 MHz clock.
-// Slots: 0 entry, 1 tables built, 2 prologue done, 3 first pages requested, 5 last page consumed, 4 record
-// stores complete, 8 first arrival done, 9/10 around the last merge the wave did, 6 done; slot 7 holds the
-// number of the die (XCC_ID register) the wave ran on.
-__device__ long long g_stamps[kMaxWaveSlots][12];
-#define JD_STAMP(w, i) do { if ((threadIdx.x & 63) == 0) { g_stamps[(w)][(i)] = wall_clock64(); \
-    if ((i) == 0) g_stamps[(w)][7] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11)); } } while (0)
-#else
-#define JD_STAMP(w, i) do { } while (0)
-#endif
 
 // meta word of a stage
 constexpr int kMetaValidMask = 0x1f;
@@ -223,7 +207,7 @@ struct Wave {
         int r = cur.r + 1;
         if (r >= live) {  // seq_lens changed under the kernel: stay in bounds, flag it
             r = live - 1;
-            if (lane == 0) atomicOr(&p.header[kHdrBadInput], 4);
+            if (lane == 0) atomicOr(&p.header[kHdrBadInput], kBadLensMoved);
         }
         // The list was stored earlier in this kernel, so the compiler will not take it through the scalar
         // path by itself; a vector load here would make it drain the page ring.  The block's own stores
@@ -465,9 +449,7 @@ struct Wave {
         if (old != w1 - w0) return;
         if (lane == 0) __hip_atomic_store(p.counters + bkv, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         asm volatile("" ::: "memory");  // the record loads below stay behind the counter read
-        JD_STAMP(wave, 9);
         merge(bkv, a, w0, w1);
-        JD_STAMP(wave, 10);
     }
 
     // Log-sum-exp merge of the pieces of one stream, by one wave.  The G*D accumulator floats of a
@@ -602,11 +584,9 @@ struct Wave {
         const int total = u1 - u0;
         issue_stage<0>(total, rs);
         if (NS < total) plan(nx);
-        JD_STAMP(wave, 3);
         int base = 0;
         for (; base + 2 * NS < total; base += NS) steady_stage<0>();
         for (; base < total; base += NS) round_stage<0>(base, total);
-        JD_STAMP(wave, 5);
 
         // pieces of sequences shared with other waves: at most the first and the last stream of the span
         const int first_a = u0 - first_pg0;
@@ -615,13 +595,10 @@ struct Wave {
         if (first_partial || last_partial) {
             // release: the write-through record stores of this wave have completed before it is counted
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            JD_STAMP(wave, 4);
             if (first_partial) arrive(first_bkv, first_a, first_n);
-            JD_STAMP(wave, 8);
             if (last_partial) arrive(cur.last_bkv, cur.last_a, cur.last_n);
         }
-        if (bad_page && lane == 0) atomicOr(&p.header[kHdrBadInput], 2);
-        JD_STAMP(wave, 6);
+        if (bad_page && lane == 0) atomicOr(&p.header[kHdrBadInput], kBadPage);
     }
 };
 
@@ -640,7 +617,7 @@ __device__ inline int build_tables(const Params& p, int* c_cum, int* c_req, int*
     int pages = 0, live = 0;
     for (int b = b0; b < b1; ++b) {
         const int L = p.seq_lens[b];
-        if (L > p.maxp * kPage && p.header[kHdrBadInput] == 0) atomicOr(&p.header[kHdrBadInput], 1);
+        if (L > p.maxp * kPage && (p.header[kHdrBadInput] & kBadLength) == 0) atomicOr(&p.header[kHdrBadInput], kBadLength);
         const int n = pages_of(p, L);
         pages += n;
         live += n > 0;
@@ -692,15 +669,12 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
 {
     using W = Wave<D, QKB, NS>;
     __shared__ __attribute__((aligned(1024))) char ring[kWaves * W::Geo::kWaveBytes];
-
-    JD_STAMP(blockIdx.x * kWaves + (threadIdx.x >> 6), 0);
     // ---- prologue: work partition (the ring doubles as scratch until the first page is fetched) ----
     int* c_cum = reinterpret_cast<int*>(ring);
     int* c_req = c_cum + ((p.B + 1 + 63) & ~63);
     int* s_part = c_req + ((p.B + 63) & ~63);
     // (values read from LDS are wave-uniform here; saying so keeps everything derived from them on the scalar unit)
     const int live = __builtin_amdgcn_readfirstlane(build_tables(p, c_cum, c_req, s_part));
-    JD_STAMP(blockIdx.x * kWaves + (threadIdx.x >> 6), 1);
     // Waves work in groups of wg: the waves of a group walk the same (request, page) sequence, each on its
     // own kv heads (member, member + wg, ...), so that together they read neighbouring kv heads of the
     // same physical page at about the same time.  The work line is counted in group-units
@@ -777,7 +751,6 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
         }
     }
     if (partition_only || group >= active) return;
-    JD_STAMP(wave, 2);
 
     W w(p);
     w.lane = threadIdx.x & 63;
@@ -836,13 +809,6 @@ hipError_t launch(const Params& p, hipStream_t stream, int partition_only)
 
 int mfma_waves_per_cu() { return kWaves; }
 int mfma_waves_per_block() { return kWaves; }
-
-#ifdef JD_TIMING
-extern "C" int jd_debug_read_stamps(long long* host)
-{
-    return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_stamps), sizeof(long long) * kMaxWaveSlots * 12) == hipSuccess ? 0 : 1;
-}
-#endif
 
 // Waves per group: the largest power of two that divides the kv-head count and fits a block.
 int mfma_group_waves(int num_kv_heads)

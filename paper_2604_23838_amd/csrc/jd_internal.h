@@ -18,8 +18,16 @@ enum HeaderWord {
     kHdrActive = 2,     // waves that own at least one unit
     kHdrSlots = 3,      // wave slots the partial pass is launched with
     kHdrNonEmpty = 4,   // requests with at least one token
-    kHdrBadInput = 5,   // sticky flag: page id or length out of bounds seen
+    kHdrBadInput = 5,   // sticky flags, see BadInputBit
     kHdrGroup = 6,      // waves per group (fused kernel; 1 = every wave on its own)
+};
+
+// Bits of the sticky device-side input-check word header[kHdrBadInput].
+enum BadInputBit {
+    kBadLength = 1,      // a sequence length beyond 16 * max_pages_per_seq (clamped)
+    kBadPage = 2,        // a block-table entry outside [0, num_pages) (page 0 read / append skipped)
+    kBadLensMoved = 4,   // seq_lens changed while the decode kernel was walking it
+    kBadQueryRows = 8,   // a prefill request whose query rows leave [0, total_q_rows) (skipped)
 };
 
 // Device pointers and sizes every kernel receives by value.
@@ -33,8 +41,9 @@ struct Params {
     // workspace
     int32_t* header;            // [kHeaderInts]
     int32_t* cum_pages;         // [B + 1] exclusive prefix of pages per request
-    int32_t* rank;              // [B] index of request b among the non-empty ones
+    int32_t* rank;              // [B] index of request b among the non-empty ones (vector-ALU kernels only)
     int32_t* req;               // [B] request id of the r-th non-empty request
+    int32_t* order;             // [B] requests by decreasing prefill work
     int32_t* wave_start;        // [slots * 4] {r, kv, page, 0}
     float* partials;            // [slots * 2] records of G*(D+2) floats: acc[G][D], m[G], l[G]
     int32_t* counters;          // [B * Hkv] arrival counters of the fused kernel (zero between calls)
@@ -63,7 +72,7 @@ hipError_t launch_append_kv(const Params& p, const uint16_t* k_new, const uint16
                             uint16_t* v_pages, int32_t* seq_lens, const int32_t* active, hipStream_t stream);
 
 hipError_t launch_prefill(const Params& p, const uint16_t* q, const int32_t* q_lens, const int32_t* q_offsets,
-                          int max_q_len, float* out, hipStream_t stream);
+                          int total_q_rows, int max_q_len, float* out, hipStream_t stream);
 int prefill_query_blocks(int max_q_len, int G);
 
 // Wave slots each variant wants per compute unit.

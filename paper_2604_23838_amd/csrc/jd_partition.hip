@@ -50,7 +50,7 @@ __global__ __launch_bounds__(kThreads) void partition_kernel(Params p)
         if (b < p.B) {
             const int L = p.seq_lens[b];
             n = L > 0 ? (L + kPage - 1) / kPage : 0;
-            if (n > p.maxp) { n = p.maxp; atomicOr(&p.header[kHdrBadInput], 1); }
+            if (n > p.maxp) { n = p.maxp; atomicOr(&p.header[kHdrBadInput], kBadLength); }
         }
         const int2 c = carry;
         int2 inc = block_scan_inclusive(make_int2(n, n > 0 ? 1 : 0), warp_tot, tid);

@@ -91,6 +91,7 @@ struct PrefillArgs {
     const int32_t* q_lens;    // [B]
     const int32_t* q_offsets; // [B]
     float* out;               // fp32 [TQ, Hq, D]
+    int32_t tq;               // rows of q and out
     int32_t nqb;              // query blocks per (request, kv head)
     const int32_t* order;     // [B] requests by decreasing work
 };
@@ -126,16 +127,6 @@ __global__ __launch_bounds__(256) void prefill_order_kernel(Params p, const int3
 template <bool B>
 struct Flag { static constexpr bool value = B; };
 
-#ifdef JD_TIMING
-// Development aid (not built by default): shader-clock stamps of the first rounds of one block.
-constexpr int kStampRounds = 96, kStampPoints = 6;
-__device__ unsigned g_pstamps[8][kStampRounds][kStampPoints];
-#define JD_PSTAMP(i) do { if (stamping && stamp_round < kStampRounds && lane == 0) \
-        lstamps[w][stamp_round][(i)] = static_cast<unsigned>(__builtin_amdgcn_s_memtime()); } while (0)
-#else
-#define JD_PSTAMP(i) do { } while (0)
-#endif
-
 template <int D, int NT>
 __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillArgs a)
 {
@@ -159,11 +150,6 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
     // page ids of the request, two windows of 64 pages: page q sits at idring[q % 128]
     __shared__ __attribute__((aligned(256))) int32_t idring[128];
     constexpr int kWin = 64 / kSP;   // stages per window
-#ifdef JD_TIMING
-    __shared__ unsigned lstamps[8][kStampRounds][kStampPoints];
-    const bool stamping = blockIdx.x == gridDim.x / 2;
-    int stamp_round = 0;
-#endif
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -183,6 +169,11 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
     const int r0 = qb * kPrefillBlockRows;
     if (r0 >= nrows) return;
     const int qoff = uniform_load(a.q_offsets + b);
+    // the rows of the request's new tokens lie inside q and out, or the request is skipped and flagged
+    if (qoff < 0 || static_cast<int64_t>(qoff) + n > a.tq) {
+        if (threadIdx.x == 0 && (p.header[kHdrBadInput] & kBadQueryRows) == 0) atomicOr(&p.header[kHdrBadInput], kBadQueryRows);
+        return;
+    }
     const int rw0 = min(r0 + w * kWaveRows, nrows - 1);   // first row of this wave (a wave past the end repeats the last row)
     const bool wave_live = r0 + w * kWaveRows < nrows;
     const int tw0 = rw0 / p.G;                            // the token of that row
@@ -420,26 +411,17 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
     // One round: the scores of stage st, its softmax, its PV product.  The loads of stage st + kDist go
     // out among the matrix instructions of the scores.
     auto round = [&](auto steady, auto masked, auto ragged, int st) __attribute__((always_inline)) {
-        JD_PSTAMP(0);
         if (decltype(steady)::value || st + kDist - 1 < nsteps) wait_vmcnt<kInFlight>(); else wait_vmcnt<0>();
-        JD_PSTAMP(1);
         __syncthreads();   // stage st has landed; everybody is through round st - 1
-        JD_PSTAMP(2);
         // every id of window (st + kDist) / kWin - 1 has been read by now: its slot takes the window after next
         // (a window no stage of which will be issued is not fetched: no load may be in flight when the block ends)
         if ((st + kDist) % kWin == 0 && ((st + kDist) / kWin + 1) * kWin < nsteps) fill_ids((st + kDist) / kWin + 1);
         qk(st);
         issue(steady, st + kDist, ids);
         load_ids(st + kDist + 1, ids);
-        JD_PSTAMP(3);
         softmax(masked, st);
         rescale();
-        JD_PSTAMP(4);
         pv(ragged, st);
-        JD_PSTAMP(5);
-#ifdef JD_TIMING
-        ++stamp_round;
-#endif
     };
 
     // ---- prologue: the first kDist stages ----
@@ -463,15 +445,8 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
     for (; st < nsteps - 1; ++st) round(Flag<false>{}, Flag<true>{}, Flag<false>{}, st);
     round(Flag<false>{}, Flag<true>{}, Flag<true>{}, nsteps - 1);
     wait_vmcnt<0>();   // nothing of this wave's may still be on its way into LDS when the block retires
-    if (bad_seen && lane == 0) atomicOr(&p.header[kHdrBadInput], 2);
+    if (bad_seen && lane == 0) atomicOr(&p.header[kHdrBadInput], kBadPage);
 
-#ifdef JD_TIMING
-    if (stamping) {
-        __syncthreads();
-        for (int i = threadIdx.x; i < 8 * kStampRounds * kStampPoints; i += kNW * 64)
-            (&g_pstamps[0][0][0])[i] = (&lstamps[0][0][0])[i];
-    }
-#endif
     // ---- normalise and store ----
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
@@ -496,23 +471,17 @@ int prefill_query_blocks(int max_q_len, int G)
     return static_cast<int>((static_cast<int64_t>(max_q_len) * G + kPrefillBlockRows - 1) / kPrefillBlockRows);
 }
 
-#ifdef JD_TIMING
-extern "C" int jd_debug_read_pstamps(unsigned* host)
-{
-    return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_pstamps), sizeof(unsigned) * 8 * kStampRounds * kStampPoints) == hipSuccess ? 0 : 1;
-}
-#endif
 
 hipError_t launch_prefill(const Params& p, const uint16_t* q, const int32_t* q_lens, const int32_t* q_offsets,
-                          int max_q_len, float* out, hipStream_t stream)
+                          int total_q_rows, int max_q_len, float* out, hipStream_t stream)
 {
     PrefillArgs a;
-    a.q = q; a.q_lens = q_lens; a.q_offsets = q_offsets; a.out = out;
+    a.q = q; a.q_lens = q_lens; a.q_offsets = q_offsets; a.out = out; a.tq = total_q_rows;
     a.nqb = prefill_query_blocks(max_q_len, p.G);
     if (a.nqb == 0 || p.B == 0) return hipSuccess;
     if (static_cast<int64_t>(a.nqb) * p.B * p.Hkv > 0x7fffffff) return hipErrorInvalidValue;
-    a.order = p.req;   // workspace the decode call uses too: calls on a handle are stream-ordered
-    hipLaunchKernelGGL(prefill_order_kernel, dim3((p.B + 255) / 256), dim3(256), 0, stream, p, q_lens, p.req);
+    a.order = p.order;
+    hipLaunchKernelGGL(prefill_order_kernel, dim3((p.B + 255) / 256), dim3(256), 0, stream, p, q_lens, p.order);
     const dim3 grid(static_cast<unsigned>(a.nqb * p.B * p.Hkv));
     if (p.D == 128)
         hipLaunchKernelGGL((prefill_kernel<128, 2>), grid, dim3(kNW * 64), 0, stream, p, a);

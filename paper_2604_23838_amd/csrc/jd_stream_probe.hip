@@ -1,8 +1,10 @@
-// Plain streaming kernels of known traffic: a read-only sweep and a copy.  They give the
-// benchmark a measured ceiling for HBM reads next to the published peak, and give the
-// profiler's byte counters a kernel of known size to be scaled against.
-#include "../../include/jigsaw_decode.h"
+// Benchmark helpers.  Plain streaming kernels of known traffic (a read-only sweep and a copy): they
+// give the benchmark a measured ceiling for HBM reads next to the published peak, and give the
+// profiler's byte counters a kernel of known size to be scaled against.  And a stream confined to a
+// subset of the compute units, on which the CU-budgeted decode call is tested and timed.
+#include "../../include/jigsaw_decode_bench.h"
 #include <hip/hip_runtime.h>
+#include <vector>
 
 namespace {
 
@@ -61,6 +63,44 @@ jd_status jd_debug_stream_copy(void* dst, const void* src, size_t bytes, void* s
     hipLaunchKernelGGL(stream_copy_kernel, dim3(grid_blocks()), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
                        static_cast<uint4*>(dst), static_cast<const uint4*>(src), bytes / 16);
     return hipGetLastError() == hipSuccess ? JD_OK : JD_ERR_HIP;
+}
+
+jd_status jd_bench_stream_create_cu_masked(int32_t num_cus, void** stream_out)
+{
+    if (!stream_out) return JD_ERR_INVALID_ARG;
+    *stream_out = nullptr;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        return JD_ERR_HIP;
+    // Every die must keep units for the workgroups the dispatcher sends it, whichever way the driver maps
+    // mask bits to dies.  With k = num_cus / 8 a multiple of 8, the bits {per_die * x + c : x < 8, c < k}
+    // give every die exactly k units both when the bits are die-major (die = bit / per_die) and when they
+    // are dealt round-robin over the dies (die = bit % 8).
+    constexpr int kDies = 8;
+    const int per_die = cus / kDies;
+    if (cus % kDies != 0 || per_die % kDies != 0 || num_cus < 64 || num_cus > cus || num_cus % 64 != 0)
+        return JD_ERR_INVALID_ARG;
+    const int k = num_cus / kDies;
+    std::vector<uint32_t> mask((cus + 31) / 32, 0u);
+    for (int x = 0; x < kDies; ++x)
+        for (int c = 0; c < k; ++c) {
+            const int bit = per_die * x + c;
+            mask[bit / 32] |= 1u << (bit % 32);
+        }
+    hipStream_t s = nullptr;
+    if (hipExtStreamCreateWithCUMask(&s, static_cast<uint32_t>(mask.size()), mask.data()) != hipSuccess) {
+        (void)hipGetLastError();
+        return JD_ERR_HIP;
+    }
+    *stream_out = s;
+    return JD_OK;
+}
+
+jd_status jd_bench_stream_destroy(void* stream)
+{
+    if (!stream) return JD_ERR_INVALID_ARG;
+    return hipStreamDestroy(static_cast<hipStream_t>(stream)) == hipSuccess ? JD_OK : JD_ERR_HIP;
 }
 
 }  // extern "C"

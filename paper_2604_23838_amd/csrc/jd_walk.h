@@ -61,7 +61,7 @@ __device__ inline Stream open_stream(const Params& p, int r, int kv)
 __device__ inline int checked_page(const Params& p, int id)
 {
     if (static_cast<unsigned>(id) >= static_cast<unsigned>(p.NP)) {
-        if ((threadIdx.x & 63) == 0) atomicOr(&p.header[kHdrBadInput], 2);
+        if ((threadIdx.x & 63) == 0) atomicOr(&p.header[kHdrBadInput], kBadPage);
         id = 0;
     }
     return id;

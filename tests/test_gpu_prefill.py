@@ -221,31 +221,108 @@ def test_hip_graph_capture_and_replay(torch_cuda, jo):
     op.close()
 
 
-def test_full_size_recompute_on_sampled_tokens(torch_cuda, jo):
-    # The benchmark's prefill workload at full size (the first 32 requests of the cfg2 draw, recomputed whole).
-    # The whole oracle output would take hours, so sampled tokens are checked one by one: token t of a causal
-    # prefill is a decode step over the first t + 1 tokens (pinned on the CPU: a one-token prefill is bitwise the
-    # decode oracle, and later tokens never influence earlier ones).
-    rng = np.random.default_rng(0)
-    lens = W.draw_seq_lens(2, rng)[:32]
-    shp = W.SHAPES[2]
-    w = W.build(W.Shape("p", 0, shp.num_q_heads, shp.num_kv_heads, shp.head_dim, 1), lens, seed=1, cfg=70)
-    ql = lens.copy()
-    q, ql, offs = prefill_inputs(w, ql, seed=2)
-    got = run_prefill(torch_cuda, w, q, ql, offs)
-    pick = np.random.default_rng(3)
+def sampled_token_check(torch_cuda, jo, w, q, ql, offs, got, per_request=3, seed=3):
+    """Token t of request b's new tokens is the decode step of its first c + t + 1 tokens (c = context): pinned
+    on the CPU (a one-token prefill is bitwise the decode oracle, later tokens never influence earlier ones)."""
+    pick = np.random.default_rng(seed)
     samples = []
-    for b in range(len(lens)):
-        L = int(lens[b])
-        fixed = [0, 1, 15, 16, 31, 32, 63, 64, 127, 128, L // 2, L - 65, L - 2, L - 1]
+    for b in range(len(ql)):
+        n = int(ql[b])
+        if n == 0:
+            continue
+        fixed = [0, 1, 15, 16, 31, 32, 63, 64, 127, 128, n // 2, n - 65, n - 2, n - 1]
         for t in fixed[:4] + fixed[-4:] if b % 4 else fixed:
-            samples.append((b, min(max(t, 0), L - 1)))
-        for t in pick.integers(0, L, size=3):
+            samples.append((b, min(max(t, 0), n - 1)))
+        for t in pick.integers(0, n, size=per_request):
             samples.append((b, int(t)))
-    sb = np.array([s[0] for s in samples]); st = np.array([s[1] for s in samples])
+    sb = np.array([s_[0] for s_ in samples]); st = np.array([s_[1] for s_ in samples])
+    ctx = (w.seq_lens.astype(np.int64) - ql)[sb]
     q_dec = np.ascontiguousarray(q[offs[sb] + st])                      # [S, Hq, D]
     bt_dec = np.ascontiguousarray(w.block_table[sb])
-    len_dec = (st + 1).astype(np.int32)
+    len_dec = (ctx + st + 1).astype(np.int32)
     ref = jo.decode_attention(q_dec, w.k_pages, w.v_pages, bt_dec, len_dec)
-    ma, mr = error_report(got[offs[sb] + st], ref)
+    g = got[offs[sb] + st]
+    assert np.isfinite(g).all()
+    ma, mr = error_report(g, ref)
+    print(f"{len(samples)} sampled tokens: max-abs {ma:.3e} max-rel {mr:.3e}", flush=True)
     assert ma <= ABS_TOL and mr <= REL_TOL, (ma, mr)
+
+
+@pytest.mark.parametrize("cfg,new_turn", [(2, 0), (4, 0), (5, 0), (2, 512), (4, 512), (5, 512)])
+def test_full_size_on_sampled_tokens(torch_cuda, jo, cfg, new_turn):
+    # The benchmark's prefill workloads at full size on the three benchmark head shapes (G = 4; G = 8; head_dim 64
+    # with G = 7): the first 32 requests of the config's length draw, recomputed whole (new_turn = 0: what a
+    # migrated request costs its target) or as the context of a new 512-token turn.  The whole oracle output would
+    # take hours, so sampled tokens are checked one by one.
+    lens = W.draw_seq_lens(cfg, np.random.default_rng(0))[:32].astype(np.int32)
+    shp = W.SHAPES[cfg]
+    w = W.build(W.Shape("p", 0, shp.num_q_heads, shp.num_kv_heads, shp.head_dim, 1), lens + new_turn, seed=1, cfg=70,
+                threads=16)
+    ql = np.full(len(lens), new_turn, dtype=np.int32) if new_turn else lens.copy()
+    q, ql, offs = prefill_inputs(w, ql, seed=2)
+    got = run_prefill(torch_cuda, w, q, ql, offs)
+    sampled_token_check(torch_cuda, jo, w, q, ql, offs, got)
+
+
+def test_prefill_and_decode_alternate_on_one_handle(torch_cuda, jo):
+    # one handle, one stream: prefill of new turns, a decode step, another prefill with other lengths, another
+    # decode step; the two calls share the handle's workspace and must leave nothing behind for each other
+    from paper_2604_23838_amd import binding as jb
+    torch = torch_cuda
+    shp = W.SHAPES[5]
+    lens = np.array([700, 33, 0, 5000, 260, 16, 2049, 1], dtype=np.int32)
+    w = W.build(shp, lens, seed=8, cfg=96)
+    B = len(lens)
+    tk, tv = bf16_dev(torch, w.k_pages), bf16_dev(torch, w.v_pages)
+    tbt, tl = torch.from_numpy(w.block_table).to("cuda:0"), torch.from_numpy(lens).to("cuda:0")
+    tqd = bf16_dev(torch, w.q)
+    op = jb.DecodeAttention(B, shp.num_q_heads, shp.num_kv_heads, shp.head_dim, w.max_pages_per_seq, w.num_pages)
+    rng = np.random.default_rng(9)
+    for step in range(3):
+        cur = lens if step == 0 else np.minimum(lens, rng.integers(0, 5001, size=B)).astype(np.int32)
+        tl.copy_(torch.from_numpy(cur))
+        ql = np.minimum(cur, rng.integers(0, 400, size=B)).astype(np.int32)
+        q, ql, offs = prefill_inputs(w, ql, seed=10 + step)
+        outp = torch.full(q.shape, 777.0, dtype=torch.float32, device="cuda:0")
+        op.prefill(bf16_dev(torch, q), tk, tv, tbt, tl, torch.from_numpy(ql).to("cuda:0"),
+                   torch.from_numpy(offs[:B].astype(np.int32)).to("cuda:0"), int(max(int(ql.max()), 1)), out=outp)
+        outd = torch.full((B, shp.num_q_heads, shp.head_dim), float("nan"), dtype=torch.float32, device="cuda:0")
+        op(tqd, tk, tv, tbt, tl, outd)
+        torch.cuda.synchronize()
+        check(outp.cpu().numpy(), jo.prefill_attention(q, w.k_pages, w.v_pages, w.block_table, cur, ql, offs), ql, offs)
+        refd = jo.decode_attention(w.q, w.k_pages, w.v_pages, w.block_table, cur)
+        gd = outd.cpu().numpy()
+        assert np.isfinite(gd).all()
+        ma, mr = error_report(gd, refd)
+        assert ma <= ABS_TOL and mr <= REL_TOL, (step, ma, mr)
+    op.check_flags()
+    op.close()
+
+
+def test_query_rows_outside_the_buffers_are_skipped_and_flagged(torch_cuda, jo):
+    # a request whose offset and length leave [0, TQ) is not computed at all (nothing of it is read or written)
+    # and raises the sticky flag; its neighbours are unaffected
+    from paper_2604_23838_amd import binding as jb
+    torch = torch_cuda
+    w = W.gen_config(1, 0)
+    ql = np.array([5, 20, 0, 64], dtype=np.int32)
+    q, ql, offs = prefill_inputs(w, ql, seed=4)
+    TQ = q.shape[0]
+    s = w.shape
+    for bad_off in (TQ - 10, -3):
+        o2 = offs[:4].astype(np.int32).copy()
+        o2[1] = bad_off                         # request 1 (20 new tokens) would run past the end / start before 0
+        op = jb.DecodeAttention(s.batch, s.num_q_heads, s.num_kv_heads, s.head_dim, w.max_pages_per_seq, w.num_pages)
+        out = torch.full(q.shape, 777.0, dtype=torch.float32, device="cuda:0")
+        op.prefill(bf16_dev(torch, q), bf16_dev(torch, w.k_pages), bf16_dev(torch, w.v_pages),
+                   torch.from_numpy(w.block_table).to("cuda:0"), torch.from_numpy(w.seq_lens).to("cuda:0"),
+                   torch.from_numpy(ql).to("cuda:0"), torch.from_numpy(o2).to("cuda:0"), 64, out=out)
+        torch.cuda.synchronize()
+        with pytest.raises(jb.JdError) as e:
+            op.check_flags()
+        assert e.value.status == jb.JD_ERR_BAD_INPUT and "query rows" in str(e.value)
+        op.close()
+        got = out.cpu().numpy()
+        ql_ok = ql.copy(); ql_ok[1] = 0
+        ref = jo.prefill_attention(q, w.k_pages, w.v_pages, w.block_table, w.seq_lens, ql_ok, offs)
+        check(got, ref, ql_ok, offs)            # request 1's rows still hold the sentinel, the others are right
