@@ -109,6 +109,28 @@ jd_status jd_decode_attention(jd_handle *h, const void *q, const void *k_pages, 
                               void *stream);
 
 /*
+ * jd_decode_attention for callers that cannot allocate device memory or hold a handle: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, arguments,
+ * layouts and result as jd_decode_attention on a handle created with `cfg` (the kernels are the same);
+ * what the handle keeps in its allocated workspace (work-partition tables, arrival counters, split-KV
+ * partial records) lives in a 12 MiB array in the library's device image instead, of which every GPU
+ * the process uses holds its own copy until the process ends.  The call allocates nothing and frees
+ * nothing, on the device or through any library, and only enqueues on `stream` (a small kernel that
+ * clears the counters the array kept from the previous call, then the decode kernel).
+ *   JD_ERR_UNSUPPORTED   cfg needs more workspace than the array holds (the message says how much; all
+ *                        benchmark shapes fit; a group size of 16 with head_dim 128 on all compute units
+ *                        does not), or any reason jd_create would give
+ *   JD_ERR_INVALID_ARG   as for jd_decode_attention; also when the first call on a device comes inside a
+ *                        stream capture (that call resolves the array's address, which cannot be captured)
+ * Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two
+ * threads) race; order them.  Device-side input checks keep every access in bounds as in
+ * jd_decode_attention, but their sticky flag is cleared by the next call and reported nowhere.
+ */
+jd_status jd_decode_attention_static(const jd_config *cfg, const void *q, const void *k_pages, const void *v_pages,
+                                     const int32_t *block_table, const int32_t *seq_lens, float *out,
+                                     void *stream);
+
+/*
  * The write half of a decode step: append one token per active request to the paged cache and
  * bump its length, so that the jd_decode_attention call that follows attends over it (a decode
  * forward step processes the active decoding requests and grows their KV cache by one token:

@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libjigsaw_decode.so")
 JD_OK, JD_ERR_INVALID_ARG, JD_ERR_UNSUPPORTED, JD_ERR_HIP, JD_ERR_BAD_INPUT = range(5)
 
 # the product ABI (include/jigsaw_decode.h) and the inspection / measurement calls (include/jigsaw_decode_bench.h)
-EXPORTS = ("jd_validate_config", "jd_workspace_bytes", "jd_create", "jd_decode_attention", "jd_append_kv",
+EXPORTS = ("jd_validate_config", "jd_workspace_bytes", "jd_create", "jd_decode_attention",
+           "jd_decode_attention_static", "jd_append_kv",
            "jd_prefill_attention", "jd_check_device_flags", "jd_destroy", "jd_last_error_string")
 BENCH_EXPORTS = ("jd_debug_partition", "jd_debug_schedule", "jd_wave_slots", "jd_debug_stream_read",
                  "jd_debug_stream_copy", "jd_bench_decode_attention_vector", "jd_bench_stream_create_cu_masked",
@@ -61,6 +62,8 @@ def lib():
         l.jd_create.restype = C.c_int
         l.jd_decode_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
         l.jd_decode_attention.restype = C.c_int
+        l.jd_decode_attention_static.argtypes = [C.POINTER(jd_config), vp, vp, vp, vp, vp, vp, vp]
+        l.jd_decode_attention_static.restype = C.c_int
         l.jd_append_kv.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
         l.jd_append_kv.restype = C.c_int
         l.jd_prefill_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_int32, C.c_int32, vp, vp]
@@ -116,6 +119,13 @@ def jd_decode_attention(handle, q, k_pages, v_pages, block_table, seq_lens, out,
     st = lib().jd_decode_attention(handle, q, k_pages, v_pages, block_table, seq_lens, out, stream)
     if st != JD_OK:
         raise JdError(st, jd_last_error_string(handle))
+
+
+def jd_decode_attention_static(cfg: jd_config, q, k_pages, v_pages, block_table, seq_lens, out, stream=0) -> None:
+    """jd_decode_attention without a handle or any allocation; device addresses (ints)."""
+    st = lib().jd_decode_attention_static(C.byref(cfg), q, k_pages, v_pages, block_table, seq_lens, out, stream)
+    if st != JD_OK:
+        raise JdError(st, jd_last_error_string(None))
 
 
 def jd_append_kv(handle, k_new, v_new, k_pages, v_pages, block_table, seq_lens, active=None, stream=0) -> None:

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 
@@ -144,6 +145,60 @@ jd_status check_decode_args(jd_handle* h, const void* q, const void* k_pages, co
     return JD_OK;
 }
 
+// ---- the allocation-free entry point's workspace ---------------------------------------------------
+// jd_decode_attention_static keeps what a handle keeps in its hipMalloc'ed workspace (partition tables,
+// arrival counters, partial records) in this array instead.  Every GPU the library runs on holds its own
+// copy of it, at its own address, until the process ends.
+constexpr size_t kStaticScratchBytes = 12u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+struct StaticSlot {
+    void* ptr = nullptr;   // device address of this GPU's copy of `scratch`
+    int cus = 0;
+};
+StaticSlot g_static[kMaxDevices];
+std::mutex g_static_mutex;
+
+// Zeroes what must start a call at zero: the flag word and the arrival counters.  A kernel, not a memset,
+// so that a caller may capture the call into a graph.
+__global__ __launch_bounds__(256) void static_clear_kernel(int32_t* header, int32_t* counters, int n_counters)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < jd::kHeaderInts) header[i] = 0;
+    if (i < n_counters) counters[i] = 0;
+}
+
+// The address of the current device's copy of the scratch array and its compute-unit count, resolved
+// once per device with that device current.
+jd_status static_slot(int dev, hipStream_t stream, StaticSlot& out)
+{
+    if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, JD_ERR_UNSUPPORTED, "device index beyond the 64 the static workspace table holds");
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticSlot& slot = g_static[dev];
+    if (!slot.ptr) {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        hipError_t e = hipStreamIsCapturing(stream, &cap);
+        if (e != hipSuccess) return fail(nullptr, JD_ERR_HIP, std::string("hipStreamIsCapturing failed: ") + hipGetErrorString(e));
+        if (cap != hipStreamCaptureStatusNone)
+            return fail(nullptr, JD_ERR_INVALID_ARG, "the first jd_decode_attention_static call on a device resolves the "
+                        "workspace address and must come outside a stream capture");
+        hipDeviceProp_t prop;
+        e = hipGetDeviceProperties(&prop, dev);
+        if (e != hipSuccess) return fail(nullptr, JD_ERR_HIP, std::string("no usable HIP device: ") + hipGetErrorString(e));
+        if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+            return fail(nullptr, JD_ERR_UNSUPPORTED, std::string("built for gfx950, device is ") + prop.gcnArchName);
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(nullptr, JD_ERR_HIP, std::string("hipGetSymbolAddress failed: ") + hipGetErrorString(e));
+        slot.cus = prop.multiProcessorCount;
+        slot.ptr = ptr;
+    }
+    out = slot;
+    return JD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -216,6 +271,42 @@ jd_status jd_decode_attention(jd_handle* h, const void* q, const void* k_pages, 
     // one launch: work partition, split-KV partial pass and combine
     const hipError_t e = jd::launch_fused_mfma(p, static_cast<hipStream_t>(stream), 0);
     if (e != hipSuccess) return fail(h, JD_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
+    return JD_OK;
+}
+
+jd_status jd_decode_attention_static(const jd_config* cfg, const void* q, const void* k_pages, const void* v_pages,
+                                     const int32_t* block_table, const int32_t* seq_lens, float* out, void* stream)
+{
+    std::string msg;
+    if (jd_status st = validate(cfg, msg)) return fail(nullptr, st, msg);
+    if (jd_status st = check_decode_args(nullptr, q, k_pages, v_pages, block_table, seq_lens, out)) return st;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(nullptr, JD_ERR_HIP, std::string("hipGetDevice failed: ") + hipGetErrorString(e));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    StaticSlot slot;
+    if (jd_status st = static_slot(dev, s, slot)) return st;
+    const int slots = wave_slots(effective_cus(*cfg, slot.cus));
+    const Layout lay = make_layout(*cfg, slots);
+    if (lay.total > kStaticScratchBytes)
+        return fail(nullptr, JD_ERR_UNSUPPORTED, "this configuration needs " + std::to_string(lay.total) +
+                    " bytes of workspace, the static array holds " + std::to_string(kStaticScratchBytes) +
+                    " (use a handle, or a smaller cu_budget)");
+    jd::Params p;
+    fill_params(p, static_cast<char*>(slot.ptr), lay, *cfg, slots);
+    p.q = static_cast<const uint16_t*>(q);
+    p.k_pages = static_cast<const uint16_t*>(k_pages);
+    p.v_pages = static_cast<const uint16_t*>(v_pages);
+    p.block_table = block_table;
+    p.seq_lens = seq_lens;
+    p.out = out;
+    // the array keeps the last call's contents, and that call may have had another configuration
+    const int n_counters = p.B * p.Hkv;
+    const int n_clear = n_counters > jd::kHeaderInts ? n_counters : jd::kHeaderInts;
+    hipLaunchKernelGGL(static_clear_kernel, dim3((n_clear + 255) / 256), dim3(256), 0, s, p.header, p.counters, n_counters);
+    e = hipGetLastError();
+    if (e == hipSuccess) e = jd::launch_fused_mfma(p, s, 0);
+    if (e != hipSuccess) return fail(nullptr, JD_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
     return JD_OK;
 }
 

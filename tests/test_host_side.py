@@ -65,6 +65,9 @@ def test_null_handle_and_pointer_errors_without_gpu():
     lib = jb.lib()
     assert lib.jd_decode_attention(None, 1, 1, 1, 1, 1, 1, None) == jb.JD_ERR_INVALID_ARG
     assert lib.jd_prefill_attention(None, 1, 1, 1, 1, 1, 1, 1, 16, 16, 1, None) == jb.JD_ERR_INVALID_ARG
+    assert lib.jd_decode_attention_static(None, 1, 1, 1, 1, 1, 1, None) == jb.JD_ERR_INVALID_ARG
+    import ctypes
+    assert lib.jd_decode_attention_static(ctypes.byref(good_config()), 16, 16, None, 16, 16, 16, None) == jb.JD_ERR_INVALID_ARG
     assert lib.jd_append_kv(None, 1, 1, 1, 1, 1, 1, None, None) == jb.JD_ERR_INVALID_ARG
     assert lib.jd_check_device_flags(None, None) == jb.JD_ERR_INVALID_ARG
     assert lib.jd_debug_partition(None, None, None, None, None, None) == jb.JD_ERR_INVALID_ARG
