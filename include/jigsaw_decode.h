@@ -55,8 +55,8 @@ typedef struct {
     int32_t max_pages_per_seq; /* MAXP: row stride (in entries) of block_table */
     int32_t num_pages;         /* NP: pages in k_pages / v_pages; page ids are checked against it */
     float softmax_scale;       /* 0 means 1 / sqrt(D) */
-    int32_t cu_budget;         /* 0: the library's choice (all compute units; three quarters of them with
-                                  head_dim 128, where that already saturates HBM); otherwise the number of
+    int32_t cu_budget;         /* 0: the library's choice (three quarters of the compute units with head_dim 128,
+                                  13/16 of them with head_dim 64: that already saturates HBM); otherwise the number of
                                   one-per-compute-unit workgroups the decode kernel is launched with (spatial
                                   sharing with a co-located job; Sub-stage Multiplexing, "Dynamic Resource
                                   Allocation") */

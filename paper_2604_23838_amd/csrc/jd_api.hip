@@ -94,10 +94,12 @@ constexpr int kAssumedCus = 256;  // MI355X; used only by the pure-host size que
 int effective_cus(const jd_config& c, int device_cus)
 {
     if (c.cu_budget > 0) return c.cu_budget < device_cus ? c.cu_budget : device_cus;
-    // measured: with 128-wide heads three quarters of the compute units already keep HBM saturated,
-    // and the step is 2-3 % faster without the contention of the rest (which stay free for a co-located job)
+    // measured: three quarters of the compute units (13/16 with 64-wide heads) already keep HBM saturated,
+    // and the step is 2-4 % faster without the contention of the rest (with all units busy the dies no
+    // longer get equal shares of the bandwidth and the slowest die sets the step time); the rest stay
+    // free for a co-located job
     if (c.head_dim == 128) return device_cus * 3 / 4;
-    return device_cus;
+    return device_cus * 13 / 16;
 }
 
 // Everything of Params that does not change from call to call.

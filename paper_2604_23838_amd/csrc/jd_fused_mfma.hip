@@ -438,15 +438,19 @@ struct Wave {
     }
 
     // ---- epilogue: arrival counters and last-arriver merge -------------------------------------
-    // Announce this wave's piece of stream bkv (units [a, a+n) of the work line); the last piece to
-    // arrive merges all of them.  The caller has waited for its record stores to complete.
-    __device__ inline void arrive(int bkv, int a, int n)
+    // Count this wave's piece of stream bkv (units [a, a+n) of the work line) with add = 1, or, with add = 0,
+    // look at the count of a stream whose piece was announced earlier; whoever finds every piece counted
+    // merges them.  The caller has waited for its record stores to complete.  A piece announced without
+    // an answer may have been the last to be counted, which only its own later look (add = 0) can find
+    // out; that look may also come just before another wave, which counted last, resets the counter:
+    // the stream is then merged twice, to the same bits.
+    __device__ inline void arrive(int bkv, int a, int n, int add)
     {
         const int w0 = a / span, w1 = (a + n - 1) / span;
         int old = 0;
-        if (lane == 0) old = __hip_atomic_fetch_add(p.counters + bkv, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (lane == 0) old = __hip_atomic_fetch_add(p.counters + bkv, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         old = __builtin_amdgcn_readfirstlane(old);
-        if (old != w1 - w0) return;
+        if (old + add != w1 - w0 + 1) return;
         if (lane == 0) __hip_atomic_store(p.counters + bkv, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         asm volatile("" ::: "memory");  // the record loads below stay behind the counter read
         merge(bkv, a, w0, w1);
@@ -584,19 +588,36 @@ struct Wave {
         const int total = u1 - u0;
         issue_stage<0>(total, rs);
         if (NS < total) plan(nx);
+
+        // Pieces of sequences shared with other waves: at most the first and the last stream of the span.
+        const int first_a = u0 - first_pg0;
+        const bool first_partial = first_pg0 > 0 || first_a + first_n > u1;
+        // When the first stream ends inside the span, its piece (the stream's last) is stored early in the
+        // span.  Vector memory operations complete in issue order, so once NS - 1 further stages have gone
+        // through the steady wait the record stores are known to have completed, and the piece is announced
+        // right there, without draining the ring and without waiting for an answer.  The wave that holds
+        // the stream's earlier piece then finds every piece in place at the end of its own span and merges;
+        // this wave owes at most one merge when it ends (for the stream its span ends in) instead of two.
+        const int first_end = first_a + first_n - u0;   // stages the first stream takes in this span, if it ends inside
+        bool announced = false;
         int base = 0;
+        if (first_partial && first_end < total) {
+            const int stop = first_end + NS - 1;
+            for (; base + 2 * NS < total && base < stop; base += NS) steady_stage<0>();
+            if (base >= stop) {
+                if (lane == 0) (void)__hip_atomic_fetch_add(p.counters + first_bkv, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                announced = true;
+            }
+        }
         for (; base + 2 * NS < total; base += NS) steady_stage<0>();
         for (; base < total; base += NS) round_stage<0>(base, total);
 
-        // pieces of sequences shared with other waves: at most the first and the last stream of the span
-        const int first_a = u0 - first_pg0;
-        const bool first_partial = first_pg0 > 0 || first_a + first_n > u1;
         const bool last_partial = cur.last_a != first_a && cur.last_a + cur.last_n > u1;
         if (first_partial || last_partial) {
             // release: the write-through record stores of this wave have completed before it is counted
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            if (first_partial) arrive(first_bkv, first_a, first_n);
-            if (last_partial) arrive(cur.last_bkv, cur.last_a, cur.last_n);
+            if (first_partial) arrive(first_bkv, first_a, first_n, announced ? 0 : 1);
+            if (last_partial) arrive(cur.last_bkv, cur.last_a, cur.last_n, 1);
         }
         if (bad_page && lane == 0) atomicOr(&p.header[kHdrBadInput], kBadPage);
     }
