@@ -85,28 +85,34 @@ def main() -> int:
 
     def timed_region(o, t, out_, steps, warmup, vector=False):
         """`warmup` untimed steps, then exactly `steps` steps between two synchronisations.  HIP events on the
-        launch stream bracket every 8th of them (an event record costs stream time, so bracketing every step
-        would slow down the very steps being measured).  Returns (ms per step by the wall clock, average ms of a
-        bracketed step by the events)."""
-        every = 8
+        launch stream bracket every other run of 8 consecutive steps (an event record costs a few microseconds
+        of stream time, so bracketing every step would slow down the very steps being measured and charge
+        the record to them).  Returns (ms per step by the wall clock, average ms of a bracketed step by the
+        events: the kernel's launch duration including the gap to the next launch)."""
+        run = 8
         with torch.cuda.stream(stream):
             for _ in range(warmup):
                 o(*t, out_, vector_kernels=vector)
             torch.cuda.synchronize()
             evs = []
             t_start = time.perf_counter()
-            for i in range(steps):
-                if i % every == 0:
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            i = 0
+            while i < steps:
+                n = min(run, steps - i)
+                bracket = (i // run) % 2 == 0
+                if bracket:
+                    e0 = torch.cuda.Event(enable_timing=True)
                     e0.record(stream)
+                for _ in range(n):
                     o(*t, out_, vector_kernels=vector)
+                if bracket:
+                    e1 = torch.cuda.Event(enable_timing=True)
                     e1.record(stream)
-                    evs.append((e0, e1))
-                else:
-                    o(*t, out_, vector_kernels=vector)
+                    evs.append((e0, e1, n))
+                i += n
             torch.cuda.synchronize()
             t_end = time.perf_counter()
-        kernel_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+        kernel_ms = sum(a.elapsed_time(b) for a, b, _ in evs) / sum(n for _, _, n in evs)
         return (t_end - t_start) * 1e3 / steps, kernel_ms
 
     def parity(got, ref):
@@ -285,15 +291,38 @@ def main() -> int:
 
     if args.sweep == "cu":
         # the paper bounds the SMs a sub-stage may use and finds small-batch rollout insensitive to them
-        # (Sub-stage Multiplexing, "Compute Resource Utilization"); the same experiment with the library's CU budget
+        # (Sub-stage Multiplexing, "Compute Resource Utilization"); the same experiment with the library's CU budget,
+        # on an ordinary stream (the grid alone is sized to the budget) and on a stream whose CU mask confines it
+        # to that many units (the analogue of the SM partition a co-located sub-stage would be given)
         cus = torch.cuda.get_device_properties(0).multi_processor_count
         rows = []
         for pct in (25, 50, 75, 100):
-            o2 = make_op(w, cus * pct // 100)
+            n_cus = cus * pct // 100
+            o2 = make_op(w, n_cus)
             us = time_steps(o2, sl)
+            row = {"cu_pct": pct, "cu_budget": n_cus, "us_per_step": round(us, 2),
+                   "kv_tb_per_s": round(kv_bytes / us / 1e6, 4)}
+            try:
+                hs = jb.jd_bench_stream_create_cu_masked(n_cus)
+            except jb.JdError as e:
+                row["masked_stream"] = f"refused: {e}"
+            else:
+                ms_ = torch.cuda.ExternalStream(hs)
+                with torch.cuda.stream(ms_):
+                    for _ in range(10):
+                        o2(q, kp, vp, bt, sl, out)
+                    ms_.synchronize()
+                    t0_ = time.perf_counter()
+                    for _ in range(60):
+                        o2(q, kp, vp, bt, sl, out)
+                    ms_.synchronize()
+                    us_m = (time.perf_counter() - t0_) * 1e6 / 60
+                torch.cuda.synchronize()
+                jb.jd_bench_stream_destroy(hs)
+                row["masked_stream_us_per_step"] = round(us_m, 2)
+                row["masked_stream_kv_tb_per_s"] = round(kv_bytes / us_m / 1e6, 4)
             o2.close()
-            rows.append({"cu_pct": pct, "cu_budget": cus * pct // 100, "us_per_step": round(us, 2),
-                         "kv_tb_per_s": round(kv_bytes / us / 1e6, 4)})
+            rows.append(row)
         result["cu_budget_sweep"] = rows
     if args.sweep == "batch":
         # the effective batch shrinks as short responses finish (Motivation, "Varied Decoding Lengths"):
