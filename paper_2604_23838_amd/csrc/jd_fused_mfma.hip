@@ -85,6 +85,20 @@ __device__ inline void dma16(unsigned lds_addr, unsigned lane_off, const void* b
                  :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
 }
 
+// The direct loads of one tensor's page, or of both tensors' pages when they fit the instruction's offset range:
+// one LDS base in m0, the j-th load 1 KiB further on.  The instruction offset moves the global address and
+// the LDS address alike, so the per-lane source offsets come with j KiB taken off (see init_lane_tables).
+__device__ inline void dma16x4(unsigned lds_addr, unsigned o0, unsigned o1, unsigned o2, unsigned o3, const void* base01,
+                               const void* base23)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %1, %5 nt\n\t"
+                 "global_load_lds_dwordx4 %2, %5 offset:1024 nt\n\t"
+                 "global_load_lds_dwordx4 %3, %6 offset:2048 nt\n\t"
+                 "global_load_lds_dwordx4 %4, %6 offset:3072 nt"
+                 :: "s"(lds_addr), "v"(o0), "v"(o1), "v"(o2), "v"(o3), "s"(base01), "s"(base23) : "memory");
+}
+
 template <int N>
 __device__ inline void wait_vmcnt()
 {
@@ -159,8 +173,10 @@ struct Wave {
         for (int j = 0; j < Geo::kLoadsPerTensor; ++j) {
             const int t = j * RPL + lane / CPR;
             const int cp = lane % CPR;
-            k_src[j] = t * Geo::kRowBytes + ((cp ^ kswz(t)) * 16);
-            v_src[j] = t * Geo::kRowBytes + ((cp ^ vswz(t)) * 16);
+            // load j is issued with an instruction offset of j KiB, which also moves its global address:
+            // t * kRowBytes holds exactly those j KiB, so what is left is never negative
+            k_src[j] = t * Geo::kRowBytes + ((cp ^ kswz(t)) * 16) - j * 1024;
+            v_src[j] = t * Geo::kRowBytes + ((cp ^ vswz(t)) * 16) - j * 1024;
         }
         const int qbytes = G * Geo::kRowBytes;
 #pragma unroll
@@ -294,11 +310,14 @@ struct Wave {
         const uint64_t page_off = static_cast<uint64_t>(id * static_cast<unsigned>(p.Hkv) + kv) << (kRowShift + 4);
         const char* kb = scalar_ptr(reinterpret_cast<const char*>(p.k_pages) + page_off);
         const char* vb = scalar_ptr(reinterpret_cast<const char*>(p.v_pages) + page_off);
-#pragma unroll
-        for (int j = 0; j < Geo::kLoadsPerTensor; ++j) dma16(stage + Geo::kQBytes + j * 1024, k_src[j], kb);
-#pragma unroll
-        for (int j = 0; j < Geo::kLoadsPerTensor; ++j)
-            dma16(stage + Geo::kQBytes + Geo::kPageBytes + j * 1024, v_src[j], vb);
+        if constexpr (Geo::kLoadsPerTensor == 2) {
+            // K and V of the page behind one LDS base: V's slot lies 2 KiB behind K's, so V's global base goes 2 KiB back
+            dma16x4(stage + Geo::kQBytes, k_src[0], k_src[1], v_src[0], v_src[1], kb, vb - Geo::kPageBytes);
+        } else {
+            static_assert(Geo::kLoadsPerTensor == 4, "four 1 KiB loads per tensor at head_dim 128");
+            dma16x4(stage + Geo::kQBytes, k_src[0], k_src[1], k_src[2], k_src[3], kb, kb);
+            dma16x4(stage + Geo::kQBytes + Geo::kPageBytes, v_src[0], v_src[1], v_src[2], v_src[3], vb, vb);
+        }
     }
 
     // ---- consumer -------------------------------------------------------------------------------
