@@ -82,3 +82,36 @@ def test_decode_on_a_cu_masked_stream(torch_cuda, jo, pct):
     finally:
         torch.cuda.synchronize()
         jb.jd_bench_stream_destroy(handle)
+
+
+def test_grid_larger_than_the_partition_runs_in_two_passes(torch_cuda, jo):
+    # A handle sized for 128 units on a stream confined to 64: the second half of the workgroups only starts when
+    # the first half has finished.  Nothing in the kernel waits for another workgroup, so the step completes; and the
+    # pieces that second-pass waves announce early are then the last of their streams to be counted, which is the
+    # path on which the announcing wave itself has to find that out at its end and merge.
+    from paper_2604_23838_amd import binding as jb
+    torch = torch_cuda
+    handle = jb.jd_bench_stream_create_cu_masked(64)
+    stream = torch.cuda.ExternalStream(handle)
+    try:
+        for w in (W.gen_config(3, 1, threads=16), W.build(W.SHAPES[5], W.draw_seq_lens(5, np.random.default_rng(4))[:300],
+                                                          seed=4, cfg=97, threads=16)):
+            s = w.shape
+            t = to_dev(torch, arrays(w))
+            ref = jo.decode_attention(*arrays(w))
+            op = jb.DecodeAttention(s.batch, s.num_q_heads, s.num_kv_heads, s.head_dim, w.max_pages_per_seq, w.num_pages,
+                                    cu_budget=128)
+            out = torch.full((s.batch, s.num_q_heads, s.head_dim), float("nan"), dtype=torch.float32, device="cuda:0")
+            torch.cuda.synchronize()
+            for rep in range(2):
+                with torch.cuda.stream(stream):
+                    op(*t, out)
+                stream.synchronize()
+                check(out.cpu().numpy(), ref, f"{s.name}: 128 workgroups on 64 units, call {rep}")
+                out.fill_(float("nan"))
+                torch.cuda.synchronize()
+            op.check_flags(stream)
+            op.close()
+    finally:
+        torch.cuda.synchronize()
+        jb.jd_bench_stream_destroy(handle)

@@ -53,6 +53,42 @@ def test_static_entry_point_matches_the_handle_twice(torch_cuda, jo):
         assert np.array_equal(got_static.view(np.uint32), got_handle.view(np.uint32)), name
 
 
+def test_static_entry_point_under_graph_capture(torch_cuda, jo):
+    # the callers this entry point is for: captured once (after a first call outside the capture has resolved the
+    # array's address), replayed with the program's own eager work in between and new lengths in the captured buffer
+    from paper_2604_23838_amd import binding as jb
+    torch = torch_cuda
+    w = W.build(W.SHAPES[5], np.array([300, 2500, 17, 64, 1200, 8000], dtype=np.int32), seed=6, cfg=93)
+    s = w.shape
+    t = to_dev(torch, arrays(w))
+    cfg = jb.jd_config(s.batch, s.num_q_heads, s.num_kv_heads, s.head_dim, 16, w.max_pages_per_seq, w.num_pages, 0.0, 0)
+    out = torch.zeros((s.batch, s.num_q_heads, s.head_dim), dtype=torch.float32, device="cuda:0")
+
+    def call():
+        jb.jd_decode_attention_static(cfg, t[0].data_ptr(), t[1].data_ptr(), t[2].data_ptr(), t[3].data_ptr(),
+                                      t[4].data_ptr(), out.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        call()
+    rng = np.random.default_rng(2)
+    lens = w.seq_lens.copy()
+    for rep in range(4):
+        if rep:
+            lens = np.minimum(w.seq_lens, rng.integers(1, 8001, size=s.batch)).astype(np.int32)
+            t[4].copy_(torch.from_numpy(lens))
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        check(out.cpu().numpy(), jo.decode_attention(w.q, w.k_pages, w.v_pages, w.block_table, lens), f"static entry point, replay {rep}")
+
+
 def test_static_entry_point_rejects_what_does_not_fit(torch_cuda):
     from paper_2604_23838_amd import binding as jb
     torch = torch_cuda
