@@ -1,4 +1,8 @@
-"""Reference statement of the work partition (integer work).  TEST INFRASTRUCTURE ONLY.
+"""Host model of the work partition (integer work).  TEST INFRASTRUCTURE ONLY.
+
+What fixes the partition is validity (every unit owned once, equal shares), which the GPU tests check on the
+library's own tables without this module; the model below states one valid rule in plain loops and the CPU
+suite checks that it has that property.
 
 The GPU library cuts one decode step's work into equal shares: the units
 (request b, kv head, page), ordered request-major, then kv head, then page, form a
