@@ -46,6 +46,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) char lds_char;
@@ -155,7 +156,7 @@ struct Wave {
     int meta[NS], dest[NS];
     bool bad_page = false;
     Cursor cur;
-    Planned nx, rs[NS];
+    Planned nx, nx2, rs[NS];
     // consumer state (lane = query row q = lane % 16; token group tg = lane / 16)
     bf16x8 qreg[D / 32];
     f32x4 acc[D / 16];
@@ -404,6 +405,73 @@ struct Wave {
         if (mt & kMetaLast) finalize(mt, dest[S]);
     }
 
+    // Two full pages from the middle of one segment, in slots S and S + 1, as one softmax update over their 32
+    // tokens.  A wave is alone on its SIMD, so every latency in the chain LDS read -> scores -> maximum ->
+    // exponentials -> P.V is idle time; two pages side by side give the scheduler independent work to fill it,
+    // and the row maximum, the rescale and the bookkeeping of the running sum are paid once.  The 8 tokens a
+    // lane holds of the two pages are one k-group of a 32-deep contraction, so P.V takes half the instructions.
+    template <int S>
+    __device__ inline void consume_pair()
+    {
+        lds_char* st0 = lds_ptr + S * Geo::kStageBytes + Geo::kQBytes;
+        lds_char* st1 = st0 + Geo::kStageBytes;
+        bf16x8 k0[D / 32], k1[D / 32];
+#pragma unroll
+        for (int i = 0; i < D / 32; ++i) {
+            k0[i] = *reinterpret_cast<__attribute__((address_space(3))) bf16x8*>(st0 + k_rd[i]);
+            k1[i] = *reinterpret_cast<__attribute__((address_space(3))) bf16x8*>(st1 + k_rd[i]);
+        }
+        s16x4 v0[D / 16], v1[D / 16];
+#pragma unroll
+        for (int jd = 0; jd < D / 16; ++jd) {
+            v0[jd] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                reinterpret_cast<__attribute__((address_space(3))) s16x4*>(st0 + Geo::kPageBytes + v_rd[jd]));
+            v1[jd] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                reinterpret_cast<__attribute__((address_space(3))) s16x4*>(st1 + Geo::kPageBytes + v_rd[jd]));
+        }
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < D / 32; ++i) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0[i], qreg[i], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1[i], qreg[i], s1, 0, 0, 0);
+        }
+        float sc[8];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            sc[r] = s0[r] * p.scale_log2e;
+            sc[4 + r] = s1[r] * p.scale_log2e;
+        }
+        float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+        mx = rows_max(mx);
+        const float mn = fmaxf(m, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m - mn);
+        float pr[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) pr[r] = __builtin_amdgcn_exp2f(sc[r] - mn);
+        l = l * alpha + (((pr[0] + pr[1]) + (pr[2] + pr[3])) + ((pr[4] + pr[5]) + (pr[6] + pr[7])));
+        if (__builtin_amdgcn_ballot_w64(mn > m) != 0) {
+#pragma unroll
+            for (int jd = 0; jd < D / 16; ++jd)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[jd][r] *= alpha;
+        }
+        m = mn;
+        s16x8 ph, pl;   // bf16 head and bf16 remainder of the probabilities
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const __bf16 h = static_cast<__bf16>(pr[r]);
+            const __bf16 lo = static_cast<__bf16>(pr[r] - static_cast<float>(h));
+            ph[r] = __builtin_bit_cast(short, h);
+            pl[r] = __builtin_bit_cast(short, lo);
+        }
+#pragma unroll
+        for (int jd = 0; jd < D / 16; ++jd) {
+            const s16x8 vt = {v0[jd][0], v0[jd][1], v0[jd][2], v0[jd][3], v1[jd][0], v1[jd][1], v1[jd][2], v1[jd][3]};
+            acc[jd] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt), __builtin_bit_cast(bf16x8, ph), acc[jd], 0, 0, 0);
+            acc[jd] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt), __builtin_bit_cast(bf16x8, pl), acc[jd], 0, 0, 0);
+        }
+    }
+
     __device__ inline void finalize(int mt, int bkv)
     {
         const int qh = lane & 15, tg = lane >> 4;
@@ -577,7 +645,12 @@ struct Wave {
             consume<S>();
             if (i + NS < total) {
                 issue<S>(nx);                       // its block-table entry was requested a page ago
-                if (i + NS + 1 < total) plan(nx);
+                if constexpr (kPairs) {             // two units are kept planned: the second moves up
+                    nx = nx2;
+                    if (i + NS + 2 < total) plan(nx2);
+                } else {
+                    if (i + NS + 1 < total) plan(nx);
+                }
             }
         }
         if constexpr (S + 1 < NS) round_stage<S + 1>(base, total);
@@ -595,6 +668,32 @@ struct Wave {
         if constexpr (S + 1 < NS) steady_stage<S + 1>();
     }
 
+    // Two such rounds at once where the ring is deep enough to spare a slot: both pages have landed, and if they are
+    // full pages from the middle of one segment (nothing begins or ends in either) they are consumed as a pair.
+    // Two units are then kept planned (nx, nx2), so that each block-table entry is still requested a pair ahead
+    // of its use.
+    static constexpr bool kPairs = NS >= 6 && NS % 2 == 0;
+    template <int S>
+    __device__ inline void steady_pair()
+    {
+        wait_vmcnt<(NS - 2) * Geo::kLoadsPerStage>();
+        if (meta[S] == kPage && meta[S + 1] == kPage) {
+            consume_pair<S>();
+        } else {
+            consume<S>();
+            consume<S + 1>();
+        }
+        issue<S>(nx);
+        issue<S + 1>(nx2);
+        plan(nx);
+        plan(nx2);
+        if constexpr (S + 2 < NS) steady_pair<S + 2>();
+    }
+    __device__ inline void steady_round()
+    {
+        if constexpr (kPairs) steady_pair<0>(); else steady_stage<0>();
+    }
+
     // Request the block-table entries of the first stages, all at once.  Touches no LDS, so it can run
     // while the block is still busy with the partition tables.
     __device__ inline void begin()
@@ -607,6 +706,11 @@ struct Wave {
         const int total = u1 - u0;
         issue_stage<0>(total, rs);
         if (NS < total) plan(nx);
+        if constexpr (kPairs) {
+            if (NS + 1 < total) plan(nx2);
+        }
+        // a steady round issues NS units and plans as many beyond them: they must all exist
+        constexpr int kSteady = 2 * NS + (kPairs ? 1 : 0);
 
         // Pieces of sequences shared with other waves: at most the first and the last stream of the span.
         const int first_a = u0 - first_pg0;
@@ -622,13 +726,13 @@ struct Wave {
         int base = 0;
         if (first_partial && first_end < total) {
             const int stop = first_end + NS - 1;
-            for (; base + 2 * NS < total && base < stop; base += NS) steady_stage<0>();
+            for (; base + kSteady < total && base < stop; base += NS) steady_round();
             if (base >= stop) {
                 if (lane == 0) (void)__hip_atomic_fetch_add(p.counters + first_bkv, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 announced = true;
             }
         }
-        for (; base + 2 * NS < total; base += NS) steady_stage<0>();
+        for (; base + kSteady < total; base += NS) steady_round();
         for (; base < total; base += NS) round_stage<0>(base, total);
 
         const bool last_partial = cur.last_a != first_a && cur.last_a + cur.last_n > u1;
