@@ -475,11 +475,11 @@ def main() -> int:
             tx = upload(wx)
             ox = torch.empty((wx.shape.batch, wx.shape.num_q_heads, wx.shape.head_dim), dtype=torch.float32, device=dev)
             o2 = make_op(wx)
-            ms_x, kms_x = timed_region(o2, tx, ox, 100, 20)
+            ms_x, kms_x = timed_region(o2, tx, ox, 200, 100)   # clocks and TLBs settle over the first ~100 short steps
             o2.check_flags()
             o2.close()
             ach = wx.kv_bytes / (kms_x * 1e-3) / 1e9
-            e = {"workload": name, "tokens": wx.total_tokens, "kv_bytes_per_step": wx.kv_bytes, "steps": 100, "warmup": 20,
+            e = {"workload": name, "tokens": wx.total_tokens, "kv_bytes_per_step": wx.kv_bytes, "steps": 200, "warmup": 100,
                  "us_per_step": round(ms_x * 1e3, 2), "kv_tb_per_s": round(wx.kv_bytes / ms_x / 1e9, 4),
                  "pct_of_hbm_peak": round(100.0 * wx.kv_bytes / ms_x / 1e6 / HBM_PEAK_GBS, 2),
                  "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
