@@ -402,3 +402,31 @@ def test_merged_straggler_batches(torch_cuda, jo, n):
     rows = np.array(rows, dtype=np.int32)
     ref = jo.decode_attention(*arrays(w), rows=rows)
     check(got[rows[:, 0], rows[:, 1]], ref, f"merged stragglers n={n} ({len(rows)} sampled rows of {w.total_tokens} tokens)")
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(14, 2, 64), (16, 1, 64), (32, 8, 128)])
+def test_closed_forms_on_long_sequences(torch_cuda, hq, hkv, d):
+    # Closed forms where the steady loop does the work (with 64-wide heads: pairs of pages consumed as one softmax
+    # update).  A zero query gives the mean of V over exactly L tokens (integer-valued V, so the mean is known to
+    # fp32 rounding); one key that dominates all others, sitting in the middle of the sequence, returns its V row
+    # exactly, wherever the running maximum was before it arrived.
+    rng = np.random.default_rng(77)
+    for L in (511, 512, 513, 4097):
+        q0 = np.zeros((1, hq, d), dtype=np.float32)
+        k = [rng.standard_normal((L, hkv, d), dtype=np.float32)]
+        v = [rng.integers(-8, 8, size=(L, hkv, d), endpoint=True).astype(np.float32)]
+        got = run_gpu(torch_cuda, pack_paged(q0, k, v, seed=L))
+        want = v[0].astype(np.float64).mean(axis=0)                      # [hkv, d]
+        for h in range(hq):
+            assert np.abs(got[0, h] - want[h // (hq // hkv)]).max() < 2e-5, (L, h)
+    L, hot = 3000, 1717
+    q = np.zeros((1, hq, d), dtype=np.float32)
+    q[:, :, 0] = 64.0
+    k = rng.standard_normal((L, hkv, d)).astype(np.float32) * 0.25
+    k[:, :, 0] = 0.0
+    k[hot, :, 0] = 64.0                                                 # score 4096 * scale against ~0 elsewhere
+    v = rng.standard_normal((L, hkv, d), dtype=np.float32)
+    got = run_gpu(torch_cuda, pack_paged(q, [k], [v], seed=5))
+    vb = W.bf16_bits_to_f64(W.f32_to_bf16_bits(v))[hot]
+    for h in range(hq):
+        assert np.array_equal(got[0, h].astype(np.float64), vb[h // (hq // hkv)]), h
