@@ -504,6 +504,84 @@ def main() -> int:
         pe["workload"] = pe.pop("case")
         log(f"prefill: {pe['ms']} ms, frac {pe['roofline']['frac']}, parity ok={pe['parity_on_sample']['ok']}")
         extra.append(pe)
+        # CU-budgeted decode on a stream confined to half of the compute units, as one replayed graph (the paper
+        # replays one pre-recorded graph per SM budget: Sub-stage Multiplexing, "Dynamic Resource Allocation"), and
+        # the closed decode loop (KV append + attention per step) under one graph; both on the straggler batch
+        w3 = W.gen_config(3, args.seed, threads=threads)
+        s3_ = w3.shape
+        t3 = upload(w3)
+        o3 = torch.empty((s3_.batch, s3_.num_q_heads, s3_.head_dim), dtype=torch.float32, device=dev)
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        half = cus // 2 // 64 * 64
+        try:
+            hs = jb.jd_bench_stream_create_cu_masked(half)
+        except jb.JdError as e:
+            extra.append({"workload": f"cfg3 on a stream masked to {half} compute units", "error": str(e)})
+        else:
+            ms_ = torch.cuda.ExternalStream(hs)
+            op3 = make_op(w3, half)
+            with torch.cuda.stream(ms_):
+                op3(*t3, o3)
+            ms_.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=ms_):
+                op3(*t3, o3)
+            with torch.cuda.stream(ms_):
+                for _ in range(50):
+                    g.replay()
+                ms_.synchronize()
+                t0_ = time.perf_counter()
+                for _ in range(200):
+                    g.replay()
+                ms_.synchronize()
+                us_ = (time.perf_counter() - t0_) * 1e6 / 200
+            torch.cuda.synchronize()
+            e = {"workload": f"cfg3 with cu_budget {half}, one graph replayed on a stream masked to {half} of {cus} compute units",
+                 "steps": 200, "warmup": 50, "us_per_step": round(us_, 2), "kv_tb_per_s": round(w3.kv_bytes / us_ / 1e6, 4),
+                 "parity_on_sample": sampled_rows_parity(w3, o3, 128, 203)}
+            log(f"masked stream: {e['us_per_step']} us/step, parity ok={e['parity_on_sample']['ok']}")
+            extra.append(e)
+            del g
+            op3.check_flags(ms_)
+            op3.close()
+            torch.cuda.synchronize()
+            jb.jd_bench_stream_destroy(hs)
+        # closed loop: requests start 32 tokens short and grow back into pages they own; new K/V rows are fresh draws
+        steps_l = 32
+        start = np.maximum(w3.seq_lens - steps_l, 1).astype(np.int32)
+        lt = torch.from_numpy(start).to(dev)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(args.seed + 9)
+        kn = torch.randn((s3_.batch, s3_.num_kv_heads, s3_.head_dim), device=dev, generator=gen).bfloat16()
+        vn = torch.randn((s3_.batch, s3_.num_kv_heads, s3_.head_dim), device=dev, generator=gen).bfloat16()
+        opl = make_op(w3)
+        with torch.cuda.stream(stream):
+            opl.append(kn, vn, t3[1], t3[2], t3[3], lt)       # warm-up step outside the capture
+            opl(t3[0], t3[1], t3[2], t3[3], lt, o3)
+            torch.cuda.synchronize()
+            lt.copy_(torch.from_numpy(start))
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                opl.append(kn, vn, t3[1], t3[2], t3[3], lt)
+                opl(t3[0], t3[1], t3[2], t3[3], lt, o3)
+            torch.cuda.synchronize()
+            t0_ = time.perf_counter()
+            for _ in range(steps_l):
+                g.replay()
+            torch.cuda.synchronize()
+            us_ = (time.perf_counter() - t0_) * 1e6 / steps_l
+        opl.check_flags(stream)
+        opl.close()
+        # the pool now holds the appended rows: bring it back and let the oracle look at the last step's output
+        w3.k_pages = t3[1].view(torch.int16).cpu().numpy().view(np.uint16)
+        w3.v_pages = t3[2].view(torch.int16).cpu().numpy().view(np.uint16)
+        w3.seq_lens = lt.cpu().numpy()
+        e = {"workload": f"closed decode loop on cfg3: KV append + attention, {steps_l} steps as one replayed graph",
+             "steps": steps_l, "us_per_step": round(us_, 2),
+             "lengths_back_at_generated": bool((w3.seq_lens == np.maximum(start + steps_l, 1)).all()),
+             "parity_on_sample": sampled_rows_parity(w3, o3, 128, 204)}
+        log(f"decode loop: {e['us_per_step']} us/step, parity ok={e['parity_on_sample']['ok']}")
+        extra.append(e)
         result["configs"] = extra
     print(json.dumps(result))
     return 0
