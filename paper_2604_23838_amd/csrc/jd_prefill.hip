@@ -4,19 +4,22 @@
 //
 // One block of kNW waves serves one (request, kv head, block of query tokens); two blocks share a
 // compute unit, so that one's matrix work runs while the other's softmax arithmetic does.  Each wave
-// holds NT tiles of 16 query rows in registers (row r of a request's kv head is query head r % G of new
+// holds one tile of 32 query rows in registers (row r of a request's kv head is query head r % G of new
 // token r / G, packed densely whatever G is), and all waves sweep the same K/V pages, which the block stages in
 // shared LDS rings of 64-key stages with direct loads (each wave issues its share of a stage; one
 // barrier and one softmax update per stage).  The block table reaches LDS the same way, a window of
-// 64 page ids at a time, so no round waits for a table read.  Per stage and tile:
-//   S^T[key][row]  = K . Q^T (v_mfma_f32_16x16x32_bf16), online softmax in the exp2 domain,
-//   O^T[d][row]   += V^T . P^T (same instruction over two pages at once: the 8 keys a lane holds of a
-//                    page pair are one k-group of the 32-deep contraction; P as bf16 head + bf16 remainder),
-//   l[row]        += 1 . P^T   (row sums from the matrix unit, V^T replaced by ones),
-// with V read transposed from LDS.  Keys after a row's own position are excluded by selection (only
-// in the rounds that reach the diagonal); pages wholly above the block's last position are never
-// fetched.  Requests are dispatched by decreasing work (a small ranking kernel runs first), the query
-// blocks of a request heaviest first.
+// 64 page ids at a time, so no round waits for a table read.  Per stage, with 32x32 matrix tiles
+// (v_mfma_f32_32x32x16_bf16: half as many matrix instructions per FLOP as 16x16 tiles, and a SIMD issues
+// matrix and vector instructions through one port, which is what bounds this kernel):
+//   S^T[key][row]  = K . Q^T, two tiles of 32 keys; a lane ends up with 16 keys of one query row per
+//                    tile, its partner lane (l ^ 32) with the other 16,
+//   online softmax in the exp2 domain: one row per lane, one exchange with the partner per stage,
+//   O^T[d][row]   += V^T . P^T, one page (16 keys) per instruction: the 8 keys a lane holds of a page are
+//                    its k-group of the contraction, so P needs no shuffle; P as bf16 head + bf16 remainder,
+//                    V read transposed from LDS.
+// Keys after a row's own position are excluded by selection (only in the rounds that reach the
+// diagonal); pages wholly above the block's last position are never fetched.  Requests are dispatched
+// by decreasing work (a small ranking kernel runs first), the query blocks of a request heaviest first.
 #include "jd_internal.h"
 #include "jd_walk.h"
 
@@ -27,6 +30,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -34,13 +38,28 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) char lds_char;
 
 constexpr int kNW = 4;    // waves per block; two blocks share a compute unit
-constexpr int kDist = 1;  // rounds between a stage's loads and its use
-constexpr int kPrefillBlockRows = kNW * 2 * 16;   // query rows (token x head of the group) per block: 2 tiles of 16 per wave
+constexpr int kWaveRows = 32;                     // query rows of a wave: one 32-wide matrix tile
+constexpr int kPrefillBlockRows = kNW * kWaveRows;   // query rows (token x head of the group) per block
 
-__device__ inline void dma16(unsigned lds_addr, unsigned lane_off, const void* base)
+// The direct loads of one tensor's page: one LDS base in m0, the j-th load 1 KiB further on.  The instruction
+// offset moves the global address and the LDS address alike, so the per-lane source offsets come with j KiB
+// taken off.
+__device__ inline void dma_page(unsigned lds_addr, const unsigned (&o)[4], const void* base)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %1, %5\n\t"
+                 "global_load_lds_dwordx4 %2, %5 offset:1024\n\t"
+                 "global_load_lds_dwordx4 %3, %5 offset:2048\n\t"
+                 "global_load_lds_dwordx4 %4, %5 offset:3072"
+                 :: "s"(lds_addr), "v"(o[0]), "v"(o[1]), "v"(o[2]), "v"(o[3]), "s"(base) : "memory");
+}
+
+__device__ inline void dma_page(unsigned lds_addr, const unsigned (&o)[2], const void* base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %1, %3\n\t"
+                 "global_load_lds_dwordx4 %2, %3 offset:1024"
+                 :: "s"(lds_addr), "v"(o[0]), "v"(o[1]), "s"(base) : "memory");
 }
 
 __device__ inline void dma4(unsigned lds_addr, unsigned lane_off, const void* base)
@@ -55,21 +74,20 @@ __device__ inline __attribute__((address_space(3))) T* lds_ptr(unsigned addr)
     return (__attribute__((address_space(3))) T*)(uintptr_t)addr;
 }
 
-// Row maximum of the scores a lane group holds.  Plain compiler-visible maxima on purpose: the compiler
-// places the wait states that a read of a fresh matrix result needs, which it cannot do for an
-// instruction hidden in inline assembly (a hand-written v_max3 here once read scores before the matrix
-// unit had written them: right to rounding, since only the reference maximum moved, but not repeatable).
-template <int N>
-__device__ inline float row_max(const f32x4 (&s)[N])
+// Maximum of the 16 scores a lane holds of its query row in a tile, then of its partner's (lane ^ 32 holds
+// the other keys of the row).  Plain compiler-visible maxima on purpose: the compiler places the wait
+// states that a read of a fresh matrix result needs, which it cannot do for an instruction hidden in
+// inline assembly (a hand-written v_max3 here once read scores before the matrix unit had written
+// them: right to rounding, since only the reference maximum moved, but not repeatable).
+__device__ inline float row_max(const f32x16& s)
 {
-    float mx = __builtin_fmaxf(__builtin_fmaxf(s[0][0], s[0][1]), s[0][2]);
+    float mx = __builtin_fmaxf(__builtin_fmaxf(s[0], s[1]), s[2]);
 #pragma unroll
-    for (int e = 3; e < 4 * N; e += 2) {
-        const float x = s[e / 4][e % 4];
-        mx = e + 1 < 4 * N ? __builtin_fmaxf(__builtin_fmaxf(mx, x), s[(e + 1) / 4][(e + 1) % 4]) : __builtin_fmaxf(mx, x);
-    }
-    mx = rows_max(mx);   // the lanes of the other key groups hold the rest of the row
-    return mx;
+    for (int e = 3; e < 15; e += 2) mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[e]), s[e + 1]);
+    mx = __builtin_fmaxf(mx, s[15]);
+    const unsigned xb = __float_as_uint(mx);
+    const u32x2 b = __builtin_amdgcn_permlane32_swap(xb, xb, false, false);
+    return __builtin_fmaxf(__uint_as_float(b.x), __uint_as_float(b.y));
 }
 
 template <int N>
@@ -126,8 +144,10 @@ __global__ __launch_bounds__(256) void prefill_order_kernel(Params p, const int3
 
 template <bool B>
 struct Flag { static constexpr bool value = B; };
+template <int T>
+struct Tensor { static constexpr int value = T; };
 
-template <int D, int NT>
+template <int D>
 __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillArgs a)
 {
     constexpr int kSP = 4;   // pages (16 keys each) per ring stage: one barrier and one softmax update per 64 keys
@@ -135,16 +155,13 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
     constexpr int kPageBytes = kPage * kRowBytes;
     constexpr int kStageBytes = kSP * kPageBytes;             // one tensor's share of a stage
     constexpr int kHalfParts = kPageBytes / 1024;             // 1 KiB direct loads per page and tensor: 4 (D=128) or 2 (D=64)
-    constexpr int kLoadsPerWave = kSP * kHalfParts / kNW;     // direct loads a wave issues per stage and tensor
-    constexpr int kPageStride = kNW / kHalfParts;             // pages between two parts of a wave
-    static_assert(kNW % kHalfParts == 0 && kLoadsPerWave >= 1, "a wave keeps one part index");
+    static_assert(kSP == kNW, "every wave loads one page of a stage");
     constexpr int CPR = kRowBytes / 16, RPL = 1024 / kRowBytes;
     constexpr int kRowShift = D == 128 ? 8 : 7;
     constexpr float kNegInf = -__builtin_inff();
-    // K and V rings of kDist + 1 stages: the loads of a stage are issued kDist rounds before its round
-    constexpr int kSlots = kDist + 1;
-    constexpr int kInFlight = (kDist - 1) * 2 * kLoadsPerWave;   // a wave's loads of the last kDist - 1 rounds
-    static_assert(kDist * 2 * kLoadsPerWave <= 63, "vmcnt is a 6-bit counter");
+    // K and V rings of two stages each; the loads of a stage are in flight for one round (see the rounds below)
+    constexpr int kSlots = 2;
+    static_assert(2 * 2 * kHalfParts <= 63, "vmcnt is a 6-bit counter");
     __shared__ __attribute__((aligned(1024))) char kring[kSlots * kStageBytes];
     __shared__ __attribute__((aligned(1024))) char vring[kSlots * kStageBytes];
     // page ids of the request, two windows of 64 pages: page q sits at idring[q % 128]
@@ -162,8 +179,6 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
     if (n > L) n = L;                      // malformed: more new tokens than the cache holds
     const int c = L - n;                   // tokens of context in front of the new ones
     // query rows of the request: row r is head r % G of new token r / G (no padding of the group)
-    constexpr int kWaveRows = NT * 16;
-    static_assert(kNW * kWaveRows == kPrefillBlockRows, "the launch and the kernel agree on the rows of a block");
     const int nrows = n * p.G;
     const int qb = a.nqb - 1 - static_cast<int>(blockIdx.x % a.nqb);   // heaviest query block first
     const int r0 = qb * kPrefillBlockRows;
@@ -181,29 +196,46 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
     const int pend = blk_last / kPage + 1;                // pages the block sweeps (<= npages)
     const int nsteps = (pend + kSP - 1) / kSP;            // stages of kSP pages
 
-    // ---- lane tables (same placement as the decode kernel: rows XOR-swizzled by token) ----
-    const int t16 = lane % 16, kg = lane / 16;
-    unsigned k_rd[D / 32], v_rd[D / 16];
-#pragma unroll
-    for (int i = 0; i < D / 32; ++i) k_rd[i] = t16 * kRowBytes + (((4 * i + kg) ^ (t16 & (CPR - 1))) * 16);
+    // ---- lane tables (same placement in LDS as the decode kernel: rows XOR-swizzled by token) ----
+    // lane = (kh, j32): j32 is the lane's query row in the tile and, for a matrix A operand, its key
+    // (K) or head-dimension element (V^T); kh picks the 8-wide half of a 16-deep contraction step.
+    const int j32 = lane % 32, kh = lane / 32, t16 = lane % 16;
+    // K as A operand of step i: key j32 of a 32-key tile (two pages), elements 16 i + 8 kh .. + 7
+    // (chunk 2 i + kh, swizzled by the token).
+    const unsigned k_base = static_cast<unsigned>(reinterpret_cast<uintptr_t>((lds_char*)kring));
+    const unsigned v_base = static_cast<unsigned>(reinterpret_cast<uintptr_t>((lds_char*)vring));
+    constexpr int NDT = D / 32, NK = D / 16;
+    // Step i toggles address bits above the half only, so one register serves every step (exclusive-or with 32 i);
+    // likewise the head-dimension tile of a V^T operand (exclusive-or with 64 dt).
+    const unsigned k_rd = k_base + (j32 / 16) * kPageBytes + t16 * kRowBytes + ((kh ^ (t16 & (CPR - 1))) * 16);
+    // V^T as A operand of head-dimension tile dt: the transposing read hands lane i of a 16-lane group element i
+    // of 4 keys; the group reads keys 4 kh .. + 3 (and 8 more for the second half of the k-group) of
+    // elements 32 dt + 16 (j32 / 16) .. + 15.
+    unsigned v_rd;
     {
-        const int row = 4 * kg + t16 / 4, cc = lane % 4;
-        const int vs = D == 128 ? ((row & 7) << 1) : (((row >> 1) & 3) << 1);
-#pragma unroll
-        for (int jd = 0; jd < D / 16; ++jd) v_rd[jd] = row * kRowBytes + (((2 * jd + cc / 2) ^ vs) * 16) + (cc % 2) * 8;
+        const int key = 4 * kh + t16 / 4, cc = t16 % 4;
+        const int vs = D == 128 ? ((key & 7) << 1) : (((key >> 1) & 3) << 1);
+        v_rd = v_base + key * kRowBytes + (((2 * (j32 / 16) + cc / 2) ^ vs) * 16) + (cc % 2) * 8;
     }
-    // this wave's share of a stage: the same 1 KiB part of K and of V of every kPageStride-th page,
-    // starting at page w / kHalfParts
-    const int part_j = w % kHalfParts;
-    const int first_page = w / kHalfParts;
+    // this wave's share of a stage: page w of K and of V, in 1 KiB direct loads; lane l of load q fills
+    // row q RPL + l / CPR, chunk position l % CPR, with the chunk the swizzle puts there.  The loads of a
+    // page differ by a constant exclusive-or at most (the row's swizzle moves with q): one register a tensor.
     unsigned src_k, src_v;
     {
-        const int t = part_j * RPL + lane / CPR, cp = lane % CPR;
+        const int t = lane / CPR, cp = lane % CPR;
         src_k = t * kRowBytes + ((cp ^ (t & (CPR - 1))) * 16);
         src_v = t * kRowBytes + ((cp ^ (D == 128 ? ((t & 7) << 1) : (((t >> 1) & 3) << 1))) * 16);
     }
-    const unsigned k_base = static_cast<unsigned>(reinterpret_cast<uintptr_t>((lds_char*)kring));
-    const unsigned v_base = static_cast<unsigned>(reinterpret_cast<uintptr_t>((lds_char*)vring));
+    auto page_sources = [&](auto which, unsigned (&o)[kHalfParts]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < kHalfParts; ++q) {
+            // row q RPL + t: the instruction offset supplies q KiB on both sides, the swizzle term of q RPL stays
+            const int tq = q * RPL;
+            const unsigned flip = decltype(which)::value == 0 ? (tq & (CPR - 1)) * 16u
+                                                               : (D == 128 ? ((tq & 7) << 1) : (((tq >> 1) & 3) << 1)) * 16u;
+            o[q] = (decltype(which)::value == 0 ? src_k : src_v) ^ flip;
+        }
+    };
     const char* kpool = reinterpret_cast<const char*>(p.k_pages);
     const char* vpool = reinterpret_cast<const char*>(p.v_pages);
     const int32_t* bt = p.block_table + static_cast<size_t>(b) * p.maxp;
@@ -218,248 +250,308 @@ __global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillA
         const int pg = min(win * 64 + lane, pend - 1);
         dma4(id_base + (win % 2) * 256, static_cast<unsigned>(pg) * 4u, bt);
     };
-    auto load_ids = [&](int st, int (&ids)[kLoadsPerWave]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < kLoadsPerWave; ++i)
-            ids[i] = __builtin_amdgcn_readfirstlane(idring[(st * kSP + first_page + kPageStride * i) & 127]);
+    auto load_id = [&](int st) __attribute__((always_inline)) -> int {
+        return __builtin_amdgcn_readfirstlane(idring[(st * kSP + w) & 127]);
     };
     bool bad_seen = false;
-    auto issue = [&](auto always, int st, int (&ids)[kLoadsPerWave]) __attribute__((always_inline)) {
-        if (!decltype(always)::value && st >= nsteps) return;
-        bool bad = false;
-#pragma unroll
-        for (int i = 0; i < kLoadsPerWave; ++i) {
-            const int j = first_page + kPageStride * i;
-            const bool ok = static_cast<unsigned>(ids[i]) < static_cast<unsigned>(p.NP);
-            bad |= !ok;
-            // a page id out of range reads page 0 and raises the sticky flag
-            const unsigned id = __builtin_amdgcn_readfirstlane(ok ? static_cast<unsigned>(ids[i]) : 0u);
-            const unsigned row = id * static_cast<unsigned>(p.Hkv) + static_cast<unsigned>(kv);
-            const uint64_t off = static_cast<uint64_t>(row) << (kRowShift + 4);
-            const unsigned dst = __builtin_amdgcn_readfirstlane((st % kSlots) * kStageBytes + j * kPageBytes + part_j * 1024);
-            dma16(k_base + dst, src_k, scalar_ptr(kpool + off));
-            dma16(v_base + dst, src_v, scalar_ptr(vpool + off));
-        }
-        bad_seen |= bad;
+    // this wave's direct loads of stage st of one tensor (K: which = 0, V: which = 1), the page with id `id`;
+    // with `sure` the stage is known to exist
+    auto issue = [&](auto which, auto sure, int st, int id) __attribute__((always_inline)) {
+        if (!decltype(sure)::value && st >= nsteps) return;
+        const bool ok = static_cast<unsigned>(id) < static_cast<unsigned>(p.NP);
+        bad_seen |= !ok;
+        // a page id out of range reads page 0 and raises the sticky flag
+        const unsigned idc = __builtin_amdgcn_readfirstlane(ok ? static_cast<unsigned>(id) : 0u);
+        const unsigned row = idc * static_cast<unsigned>(p.Hkv) + static_cast<unsigned>(kv);
+        const uint64_t off = static_cast<uint64_t>(row) << (kRowShift + 4);
+        const unsigned dst = __builtin_amdgcn_readfirstlane((st % kSlots) * kStageBytes + w * kPageBytes);
+        unsigned o[kHalfParts];
+        page_sources(which, o);
+        if (decltype(which)::value == 0) dma_page(k_base + dst, o, scalar_ptr(kpool + off));
+        else dma_page(v_base + dst, o, scalar_ptr(vpool + off));
     };
-    int ids[kLoadsPerWave];   // page ids of the next stage to issue
+    int id_k, id_v;   // page ids of this wave's page of the next K stage and of the next V stage to issue
 
-    // ---- queries of this wave: NT tiles of 16 rows, row = (token, head of the group) ----
-    bf16x8 qreg[NT][D / 32];
-    int row_pos[NT];      // position of this lane's query row in the sequence (c + token)
-    bool row_ok[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int r = r0 + w * kWaveRows + nt * 16 + t16;
-        row_ok[nt] = wave_live && r < nrows;
+    // ---- queries of this wave: 32 rows, row = (token, head of the group); B operand of step i ----
+    bf16x8 qreg[D / 16];
+    int row_pos;      // position of this lane's query row in the sequence (c + token)
+    bool row_ok;
+    {
+        const int r = r0 + w * kWaveRows + j32;
+        row_ok = wave_live && r < nrows;
         const int rc = min(r, nrows - 1);   // rows past the end repeat the last real row
         const int tk = rc / p.G, gg = rc % p.G;
-        row_pos[nt] = c + tk;
+        row_pos = c + tk;
         const uint16_t* src = a.q + (static_cast<size_t>(qoff + tk) * p.Hq + kv * p.G + gg) * D;
 #pragma unroll
-        for (int i = 0; i < D / 32; ++i)
-            qreg[nt][i] = *reinterpret_cast<const bf16x8*>(src + (4 * i + kg) * 8);
+        for (int i = 0; i < D / 16; ++i)
+            qreg[i] = *reinterpret_cast<const bf16x8*>(src + (2 * i + kh) * 8);
     }
-    f32x4 acc[NT][D / 16];
-    f32x4 lacc[NT];       // softmax denominators (every register of a lane holds its row's)
-    float m[NT], alpha[NT];
+    f32x16 acc[D / 32];   // O^T: register r of tile dt is element 32 dt + 8 (r / 4) + 4 kh + r % 4 of row j32
+    float lsum = 0.f;     // softmax denominator over this lane's keys (the partner lane holds the rest)
+    float m = kNegInf;    // reference exponent of the row's probabilities (log2 domain)
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        m[nt] = kNegInf;
-        alpha[nt] = 1.f;
-        lacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-        for (int jd = 0; jd < D / 16; ++jd) acc[nt][jd] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
+        for (int r = 0; r < 16; ++r) acc[dt][r] = 0.f;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the query loads are in before the page rings start
 
-    f32x4 sc[NT][kSP];                       // raw scores of the stage whose softmax comes next
-    u32x4 ph[NT][kSP / 2], pl[NT][kSP / 2];  // probabilities of the stage whose PV product comes next
-    const bf16x8 ones = __builtin_bit_cast(bf16x8, u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
+    f32x16 sc[2];              // raw scores of a 32-key tile, by tile parity: register r is key 8 (r / 4) + 4 kh + r % 4 of the tile
+    u32x4 ph[2][2], pl[2][2];  // probabilities of a tile, by tile parity and page: the lane's 8 keys of the page as bf16 pairs
 
-    // S^T = K Q^T of stage st for every tile (raw dot products; the scale is applied inside the exponent)
-    auto qk = [&](int st) __attribute__((always_inline)) {
-        unsigned ka[D / 32];
+    // S^T = K Q^T of tile kt of stage st (raw dot products; the scale is applied inside the exponent)
+    auto qk = [&](int st, int kt) __attribute__((always_inline)) {
+        const unsigned ka = k_rd + (st % kSlots) * kStageBytes + kt * 2 * kPageBytes;
+        f32x16 s;
 #pragma unroll
-        for (int i = 0; i < D / 32; ++i) {
-            ka[i] = k_base + (st % kSlots) * kStageBytes + k_rd[i];
-            asm volatile("" : "+v"(ka[i]));   // one add per stage; the page offset rides in the instruction
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+        for (int i = 0; i < NK; ++i) {
+            const bf16x8 kf = *lds_ptr<bf16x8>(ka ^ (i * 32));
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qreg[i], s, 0, 0, 0);
         }
+        sc[kt] = s;
+    };
+
+    // Probabilities of scores 2 j, 2 j + 1 of tile kt against the reference exponent mref: -> ph[kt], pl[kt]
+    // (bf16 head + bf16 remainder; the remainder p - head comes from one packed dot product per score:
+    // head . (-1, 0) + p), their sum joins part[j % 4].
+    // (the two constants live in scalar registers: written as an immediate, the pair (-1, 0) is encoded as
+    // the inline constant -1.0, which the instruction reads as the pair (0, -1))
+    uint32_t minus_first_bits = 0x0000bf80u, minus_second_bits = 0xbf800000u;
+    asm volatile("" : "+s"(minus_first_bits), "+s"(minus_second_bits));
+    const bf16x2 minus_first = __builtin_bit_cast(bf16x2, minus_first_bits), minus_second = __builtin_bit_cast(bf16x2, minus_second_bits);
+    auto probability_pair = [&](int kt, int j, float mref, float (&part)[4]) __attribute__((always_inline)) {
+        const int r = 2 * j;
+        f32x2 pr;
+        pr[0] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][r], p.scale_log2e, -mref));
+        pr[1] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][r + 1], p.scale_log2e, -mref));
+        part[j % 4] += pr[0];
+        part[j % 4] += pr[1];
+        const bf16x2 hi = __builtin_convertvector(pr, bf16x2);
+        f32x2 rem;
+        rem[0] = __builtin_amdgcn_fdot2_f32_bf16(hi, minus_first, pr[0], false);
+        rem[1] = __builtin_amdgcn_fdot2_f32_bf16(hi, minus_second, pr[1], false);
+        const bf16x2 lo = __builtin_convertvector(rem, bf16x2);
+        ph[kt][r / 8][(r % 8) / 2] = __builtin_bit_cast(uint32_t, hi);
+        pl[kt][r / 8][(r % 8) / 2] = __builtin_bit_cast(uint32_t, lo);
+    };
+    auto probabilities = [&](int kt, float mref) __attribute__((always_inline)) -> float {
+        float part[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int j = 0; j < kSP; ++j) {
-            bf16x8 kf[D / 32];
+        for (int j = 0; j < 8; ++j) probability_pair(kt, j, mref, part);
+        return (part[0] + part[1]) + (part[2] + part[3]);
+    };
+
+    // Keys after the row's own position (and slots past the sequence's end) are excluded by selection.
+    auto mask = [&](int st, int kt) __attribute__((always_inline)) {
+        const int key0 = (st * kSP + 2 * kt) * kPage + 4 * kh;
 #pragma unroll
-            for (int i = 0; i < D / 32; ++i) kf[i] = *lds_ptr<bf16x8>(ka[i] + j * kPageBytes);
+        for (int r = 0; r < 16; ++r)
+            if (key0 + 8 * (r / 4) + r % 4 > row_pos) sc[kt][r] = kNegInf;
+    };
+
+    // Online softmax of a tile.  Any reference exponent m gives the same result as long as nothing
+    // overflows, so the tile is first evaluated against the m the row already has (no row maximum, no
+    // rescaling of the accumulators: the common case once the first tiles have set m): `part` is that
+    // evaluation's sum.  Only when some row's probabilities have outgrown 2^16 (or m is still unset, or
+    // a sum is not a number) does the wave take the exact path: row maxima, new m, accumulators and
+    // sums rescaled, probabilities again.  The accumulators hold exactly the tiles before this one.
+    auto settle = [&](int kt, float part) __attribute__((always_inline)) {
+        if (__builtin_amdgcn_ballot_w64(!(part < 65536.f)) != 0) {
+            // the scale is positive, so the maximum can be taken before scaling; mn is finite,
+            // because position 0 is visible to every row
+            const float mx = row_max(sc[kt]);
+            const float mn = __builtin_fmaxf(m, mx * p.scale_log2e);
+            const float alpha = __builtin_amdgcn_exp2f(m - mn);
+            m = mn;
+            lsum *= alpha;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                f32x4 s = {0.f, 0.f, 0.f, 0.f};
+            for (int dt = 0; dt < D / 32; ++dt) acc[dt] *= alpha;
+            part = probabilities(kt, m);
+        }
+        lsum += part;
+    };
+
+    // V^T operands of one page of a tile: read k of the page is half k % 2 of the k-group of head-dimension tile k / 2;
+    // va is this lane's address in the tile for head-dimension tile 0
+    auto read_v = [&](unsigned va, int pg, int k, u32x4 (&vf)[2][NDT]) __attribute__((always_inline)) {
+        const int dt = k / 2, h = k % 2;
+        const u32x2 t = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            lds_ptr<s16x4>((va ^ (dt * 64)) + pg * kPageBytes + h * 8 * kRowBytes)));
+        vf[pg][dt][2 * h] = t[0];
+        vf[pg][dt][2 * h + 1] = t[1];
+    };
+
+    // O^T += V^T P^T of tile kt of stage st on its own (the last tile of a block), value rows past the
+    // sequence's end zeroed first.
+    auto pv_last = [&](int st, int kt) __attribute__((always_inline)) {
+        const int key0 = (st * kSP + 2 * kt) * kPage + 4 * kh;
+        const unsigned va = v_rd + (st % kSlots) * kStageBytes + kt * 2 * kPageBytes;
+        u32x4 vf[2][NDT];
 #pragma unroll
-                for (int i = 0; i < D / 32; ++i)
-                    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[i], qreg[nt][i], s, 0, 0, 0);
-                sc[nt][j] = s;
+        for (int pg = 0; pg < 2; ++pg) {
+#pragma unroll
+            for (int k = 0; k < 2 * NDT; ++k) read_v(va, pg, k, vf);
+            const int valid = L - (key0 + pg * kPage);   // tokens from this lane's first key on that exist (<= 0: a repeated page)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int k0 = 8 * (e / 2) + 2 * (e % 2);
+                const uint32_t keep = (k0 < valid ? 0x0000ffffu : 0u) | (k0 + 1 < valid ? 0xffff0000u : 0u);
+#pragma unroll
+                for (int dt = 0; dt < NDT; ++dt) vf[pg][dt][e] &= keep;
             }
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt)
+                acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[pg][dt]), __builtin_bit_cast(bf16x8, ph[kt][pg]), acc[dt], 0, 0, 0);
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt)
+                acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[pg][dt]), __builtin_bit_cast(bf16x8, pl[kt][pg]), acc[dt], 0, 0, 0);
         }
     };
 
-    // Online softmax of stage st: sc -> ph, pl (bf16 head + bf16 remainder, two pages side by side: the
-    // 8 keys a lane holds of a page pair are one k-group of a 32-deep contraction), m, alpha.  With
-    // `masked`, keys after a row's own position (and slots past the sequence's end) are excluded by selection.
-    auto softmax = [&](auto masked, int st) __attribute__((always_inline)) {
-        const int key0 = st * kSP * kPage;
+    // Half a round: the PV product of the tile before tile (st, KT), the softmax of tile (st, KT), the scores of
+    // the tile after it: matrix work and vector work that do not depend on each other, in one stretch of
+    // straight-line code (a SIMD overlaps the two kinds only when one wave's instruction stream offers both).
+    // The order is fixed by hand, group by group: one matrix instruction, the LDS reads that later groups need
+    // (the second page's V operands during the first page's products, each K operand three groups ahead), and a
+    // share of the 8 probability pairs; the compiler's own order bunches the matrix instructions.
+    auto half = [&](auto kt_c, auto with_pv, auto masked, auto ragged, auto sure, int st) __attribute__((always_inline)) {
+        constexpr int KT = decltype(kt_c)::value, OT = 1 - KT;
+        constexpr int NPV = decltype(with_pv)::value ? 4 * NDT : 0, NM = NPV + NK, kLead = NPV >= 3 ? 3 : 0;
+        const int st_pv = st - 1 + KT, st_qk = st + KT;   // the tile before is (st - 1, 1) or (st, 0), the tile after (st, 1) or (st + 1, 0)
+        // this lane's addresses in the two tiles (one add per tile; the rest rides in the instructions)
+        unsigned va = v_rd + (st_pv % kSlots) * kStageBytes + OT * 2 * kPageBytes;
+        unsigned ka = k_rd + (st_qk % kSlots) * kStageBytes + OT * 2 * kPageBytes;
+        asm volatile("" : "+v"(va), "+v"(ka));
+        if (decltype(masked)::value) mask(st, KT);
+        u32x4 vf[2][NDT];
+        bf16x8 kf[NK];
+        uint32_t keep[2][4];
+        if (NPV != 0) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            if (decltype(masked)::value) {
-#pragma unroll
-                for (int j = 0; j < kSP; ++j)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (key0 + j * kPage + 4 * kg + r > row_pos[nt]) sc[nt][j][r] = kNegInf;
-            }
-            // the scale is positive, so the maximum can be taken before scaling; mn is finite from the
-            // first stage on, because position 0 is visible to every row
-            const float mx = row_max<kSP>(sc[nt]);
-            const float mn = __builtin_fmaxf(m[nt], mx * p.scale_log2e);
-            alpha[nt] = __builtin_amdgcn_exp2f(m[nt] - mn);
-            m[nt] = mn;
-#pragma unroll
-            for (int j = 0; j < kSP; ++j)
-#pragma unroll
-                for (int r = 0; r < 4; r += 2) {
-                    f32x2 pr;
-                    pr[0] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[nt][j][r], p.scale_log2e, -mn));
-                    pr[1] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[nt][j][r + 1], p.scale_log2e, -mn));
-                    const bf16x2 hi = __builtin_convertvector(pr, bf16x2);
-                    const bf16x2 lo = __builtin_convertvector(pr - __builtin_convertvector(hi, f32x2), bf16x2);
-                    ph[nt][j / 2][2 * (j % 2) + r / 2] = __builtin_bit_cast(uint32_t, hi);
-                    pl[nt][j / 2][2 * (j % 2) + r / 2] = __builtin_bit_cast(uint32_t, lo);
-                }
-        }
-    };
-
-    // O^T += V^T P^T of stage st, 32 keys per instruction; the row sums of P come from the same unit
-    // (V^T replaced by ones).  With `ragged`, value rows past the sequence's end are zeroed first.
-    auto pv = [&](auto ragged, int st) __attribute__((always_inline)) {
-        const int key0 = st * kSP * kPage;
-        unsigned va[D / 16];
-#pragma unroll
-        for (int jd = 0; jd < D / 16; ++jd) {
-            va[jd] = v_base + (st % kSlots) * kStageBytes + v_rd[jd];
-            asm volatile("" : "+v"(va[jd]));
-        }
-#pragma unroll
-        for (int jp = 0; jp < kSP / 2; ++jp) {
-            bf16x8 bh[NT], bl[NT];
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                bh[nt] = __builtin_bit_cast(bf16x8, ph[nt][jp]);
-                bl[nt] = __builtin_bit_cast(bf16x8, pl[nt][jp]);
-                lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bh[nt], lacc[nt], 0, 0, 0);
-                lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bl[nt], lacc[nt], 0, 0, 0);
-            }
-            uint32_t keep[2][2];
+            for (int k = 0; k < 2 * NDT; ++k) read_v(va, 0, k, vf);
             if (decltype(ragged)::value) {
+                const int key0 = (st_pv * kSP + 2 * OT) * kPage + 4 * kh;
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int valid = L - (key0 + (2 * jp + h) * kPage);   // tokens of this page that exist (<= 0: a repeated page)
-                    keep[h][0] = (4 * kg + 0 < valid ? 0x0000ffffu : 0u) | (4 * kg + 1 < valid ? 0xffff0000u : 0u);
-                    keep[h][1] = (4 * kg + 2 < valid ? 0x0000ffffu : 0u) | (4 * kg + 3 < valid ? 0xffff0000u : 0u);
-                }
-            }
-#pragma unroll
-            for (int q4 = 0; q4 < D / 64; ++q4) {   // four 16-wide slices of the head dimension at a time
-                u32x4 vf[4];   // per lane: 4 keys of page 2 jp, then 4 keys of page 2 jp + 1
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
+                for (int pg = 0; pg < 2; ++pg) {
+                    const int valid = L - (key0 + pg * kPage);   // tokens from this lane's first key on that exist (<= 0: a repeated page)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const u32x2 t = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            lds_ptr<s16x4>(va[4 * q4 + e] + (2 * jp + h) * kPageBytes)));
-                        vf[e][2 * h] = t[0];
-                        vf[e][2 * h + 1] = t[1];
-                    }
-                if (decltype(ragged)::value) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        vf[e][0] &= keep[0][0]; vf[e][1] &= keep[0][1];
-                        vf[e][2] &= keep[1][0]; vf[e][3] &= keep[1][1];
+                        const int k0 = 8 * (e / 2) + 2 * (e % 2);
+                        keep[pg][e] = (k0 < valid ? 0x0000ffffu : 0u) | (k0 + 1 < valid ? 0xffff0000u : 0u);
                     }
                 }
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const bf16x8 vt = __builtin_bit_cast(bf16x8, vf[e]);
-                        acc[nt][4 * q4 + e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, bh[nt], acc[nt][4 * q4 + e], 0, 0, 0);
-                        acc[nt][4 * q4 + e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, bl[nt], acc[nt][4 * q4 + e], 0, 0, 0);
-                    }
             }
         }
-    };
-
-    // alpha of the last softmax is applied once the PV product issued before it is through
-    auto rescale = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            if (__builtin_amdgcn_ballot_w64(alpha[nt] != 1.f) != 0) {   // nobody's maximum moved: alpha is exactly 1 everywhere
-                lacc[nt] *= alpha[nt];
+        for (int i = 0; i < NK; ++i)
+            if (i - kLead < 0 || NPV == 0) kf[i] = *lds_ptr<bf16x8>(ka ^ (i * 32));
+        float part[4] = {0.f, 0.f, 0.f, 0.f};
+        f32x16 s;
 #pragma unroll
-                for (int jd = 0; jd < D / 16; ++jd) acc[nt][jd] *= alpha[nt];
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = 0; g < NM; ++g) {
+            if (g < NPV) {
+                const int pg = g / (2 * NDT), dt = (g % (2 * NDT)) / 2, lo = g % 2;   // head then remainder on one accumulator
+                if (decltype(ragged)::value && lo == 0) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) vf[pg][dt][e] &= keep[pg][e];
+                }
+                acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[pg][dt]),
+                                                                  __builtin_bit_cast(bf16x8, lo ? pl[OT][pg] : ph[OT][pg]), acc[dt], 0, 0, 0);
+                if (g < 2 * NDT) read_v(va, 1, g, vf);
+            } else {
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[g - NPV], qreg[g - NPV], s, 0, 0, 0);
             }
+            if (NPV != 0 && g - (NPV - kLead) >= 0 && g - (NPV - kLead) < NK) kf[g - (NPV - kLead)] = *lds_ptr<bf16x8>(ka ^ ((g - (NPV - kLead)) * 32));
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (g == j * NM / 8) probability_pair(KT, j, m, part);
+            // the second half carries the round's direct loads (K of stage st + 2, then V of stage st + 1: their
+            // slots are free since the barrier in front of it) and fetches the page id of the round after
+            if (KT == 1) {
+                if (g == 0) issue(Tensor<0>{}, sure, st + 2, id_k);
+                else if (g == 2) issue(Tensor<1>{}, sure, st + 1, id_v);
+                else if (g == 4) { id_v = id_k; id_k = load_id(st + 3); }
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
+        sc[OT] = s;
+        // the probabilities are complete before the branch of `settle` (the compiler would sink their bf16
+        // split behind it, where no matrix instruction runs)
+        asm volatile("" :: "v"(ph[KT][0]), "v"(ph[KT][1]), "v"(pl[KT][0]), "v"(pl[KT][1]));
+        settle(KT, (part[0] + part[1]) + (part[2] + part[3]));
     };
 
-    // One round: the scores of stage st, its softmax, its PV product.  The loads of stage st + kDist go
-    // out among the matrix instructions of the scores.
-    auto round = [&](auto steady, auto masked, auto ragged, int st) __attribute__((always_inline)) {
-        if (decltype(steady)::value || st + kDist - 1 < nsteps) wait_vmcnt<kInFlight>(); else wait_vmcnt<0>();
-        __syncthreads();   // stage st has landed; everybody is through round st - 1
-        // every id of window (st + kDist) / kWin - 1 has been read by now: its slot takes the window after next
+    // One round = the two 32-key tiles of stage st, software-pipelined:
+    //   first half:   PV of tile (st - 1, 1)   softmax of tile (st, 0)   scores of tile (st, 1)
+    //   middle:       every wave's loads have landed, barrier
+    //   second half:  PV of tile (st, 0)       softmax of tile (st, 1)   scores of tile (st + 1, 0)   the next loads
+    // So K of stage st + 1 and V of stage st must be in LDS at the middle of round st; they were issued at the
+    // middle of round st - 1, into the slots that K of stage st - 1 and V of stage st - 2 had left by then, and
+    // have a whole round to arrive.  One barrier per round.
+    auto round = [&](auto first, auto masked, auto ragged, auto sure, int st) __attribute__((always_inline)) {
+        half(Tensor<0>{}, Flag<!decltype(first)::value>{}, masked, Flag<false>{}, sure, st);
+        wait_vmcnt<0>();
+        __syncthreads();   // K of stage st + 1 and V of stage st have landed; everybody has left K of stage st and V of stage st - 1
+        // every id of window (st + 1) / kWin - 1 has been read by now: its slot takes the window after next
         // (a window no stage of which will be issued is not fetched: no load may be in flight when the block ends)
-        if ((st + kDist) % kWin == 0 && ((st + kDist) / kWin + 1) * kWin < nsteps) fill_ids((st + kDist) / kWin + 1);
-        qk(st);
-        issue(steady, st + kDist, ids);
-        load_ids(st + kDist + 1, ids);
-        softmax(masked, st);
-        rescale();
-        pv(ragged, st);
+        if ((st + 1) % kWin == 0 && ((st + 1) / kWin + 1) * kWin < nsteps) fill_ids((st + 1) / kWin + 1);
+        half(Tensor<1>{}, Flag<true>{}, masked, ragged, sure, st);   // past the last stage: scores of whatever the slot holds, never used
     };
 
-    // ---- prologue: the first kDist stages ----
+    // ---- prologue: K and V of stage 0, K of stage 1, the scores of the first tile ----
     fill_ids(0);
     fill_ids(1);
     wait_vmcnt<0>();
     __syncthreads();
-#pragma unroll
-    for (int x = 0; x < kDist; ++x) {
-        load_ids(x, ids);
-        issue(Flag<false>{}, x, ids);
-    }
-    load_ids(kDist, ids);
+    id_k = load_id(0);
+    issue(Tensor<0>{}, Flag<false>{}, 0, id_k);
+    issue(Tensor<1>{}, Flag<false>{}, 0, id_k);
+    id_v = load_id(1);
+    issue(Tensor<0>{}, Flag<false>{}, 1, id_v);
+    id_k = load_id(2);
+    wait_vmcnt<0>();
+    __syncthreads();
+    qk(0, 0);
 
     // ---- rounds ----
     // the softmax of stage st needs the mask once the stage reaches past the wave's first row
     const int first_masked = (c + tw0 >= kSP * kPage - 1) ? (c + tw0 - (kSP * kPage - 1)) / (kSP * kPage) + 1 : 0;
-    int st = 0;
-    // steady rounds: the stage they issue exists, no softmax needs the mask, no value row lies past the end
-    for (; st + kDist < nsteps && st < first_masked; ++st) round(Flag<true>{}, Flag<false>{}, Flag<false>{}, st);
-    for (; st < nsteps - 1; ++st) round(Flag<false>{}, Flag<true>{}, Flag<false>{}, st);
-    round(Flag<false>{}, Flag<true>{}, Flag<true>{}, nsteps - 1);
+    if (nsteps == 1) {
+        round(Flag<true>{}, Flag<true>{}, Flag<true>{}, Flag<false>{}, 0);
+    } else {
+        round(Flag<true>{}, Flag<true>{}, Flag<false>{}, Flag<false>{}, 0);
+        int st = 1;
+        // steady rounds: the stages they load exist, no softmax needs the mask, no value row lies past the end
+        for (; st < nsteps - 2 && st < first_masked; ++st) round(Flag<false>{}, Flag<false>{}, Flag<false>{}, Flag<true>{}, st);
+        for (; st < nsteps - 1; ++st) round(Flag<false>{}, Flag<true>{}, Flag<false>{}, Flag<false>{}, st);
+        round(Flag<false>{}, Flag<true>{}, Flag<true>{}, Flag<false>{}, nsteps - 1);
+    }
+    pv_last(nsteps - 1, 1);
     wait_vmcnt<0>();   // nothing of this wave's may still be on its way into LDS when the block retires
     if (bad_seen && lane == 0) atomicOr(&p.header[kHdrBadInput], kBadPage);
 
     // ---- normalise and store ----
+    {
+        const unsigned lb = __float_as_uint(lsum);
+        const u32x2 both = __builtin_amdgcn_permlane32_swap(lb, lb, false, false);   // the partner's share of the row sum
+        const float lt = __uint_as_float(both.x) + __uint_as_float(both.y);
+        if (row_ok) {
+            const int r = r0 + w * kWaveRows + j32;
+            const int tok = r / p.G, g = r % p.G;
+            const float inv = 1.f / lt;
+            float* o = a.out + (static_cast<size_t>(qoff + tok) * p.Hq + kv * p.G + g) * D + 4 * kh;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const float lt = lacc[nt][0];
-        if (!row_ok[nt]) continue;
-        const int r = r0 + w * kWaveRows + nt * 16 + t16;
-        const int tok = r / p.G, g = r % p.G;
-        const float inv = 1.f / lt;
-        float* o = a.out + (static_cast<size_t>(qoff + tok) * p.Hq + kv * p.G + g) * D + 4 * kg;
+            for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-        for (int jd = 0; jd < D / 16; ++jd)
-            *reinterpret_cast<float4*>(o + 16 * jd) =
-                make_float4(acc[nt][jd][0] * inv, acc[nt][jd][1] * inv, acc[nt][jd][2] * inv, acc[nt][jd][3] * inv);
+                for (int e = 0; e < 4; ++e)
+                    *reinterpret_cast<float4*>(o + 32 * dt + 8 * e) =
+                        make_float4(acc[dt][4 * e] * inv, acc[dt][4 * e + 1] * inv, acc[dt][4 * e + 2] * inv, acc[dt][4 * e + 3] * inv);
+        }
     }
 }
 
@@ -484,9 +576,9 @@ hipError_t launch_prefill(const Params& p, const uint16_t* q, const int32_t* q_l
     hipLaunchKernelGGL(prefill_order_kernel, dim3((p.B + 255) / 256), dim3(256), 0, stream, p, q_lens, p.order);
     const dim3 grid(static_cast<unsigned>(a.nqb * p.B * p.Hkv));
     if (p.D == 128)
-        hipLaunchKernelGGL((prefill_kernel<128, 2>), grid, dim3(kNW * 64), 0, stream, p, a);
+        hipLaunchKernelGGL((prefill_kernel<128>), grid, dim3(kNW * 64), 0, stream, p, a);
     else
-        hipLaunchKernelGGL((prefill_kernel<64, 2>), grid, dim3(kNW * 64), 0, stream, p, a);
+        hipLaunchKernelGGL((prefill_kernel<64>), grid, dim3(kNW * 64), 0, stream, p, a);
     return hipGetLastError();
 }
 
