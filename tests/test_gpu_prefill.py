@@ -84,6 +84,38 @@ def test_single_new_token_equals_the_decode_entry_point(torch_cuda, jo):
     assert np.abs(got - dec.cpu().numpy()).max() <= 1e-5
 
 
+def _set_keys_along(w, b, direction, gain):
+    """Keys of request b become gain[t] * direction at position t (every kv head), through the block table."""
+    for t in range(int(w.seq_lens[b])):
+        page, slot = int(w.block_table[b, t // 16]), t % 16
+        w.k_pages[page, :, slot, :] = W.f32_to_bf16_bits((gain[t] * direction).astype(np.float32))
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(32, 8, 128), (14, 2, 64)])
+def test_scores_that_outgrow_the_reference_exponent(torch_cuda, jo, hq, hkv, d):
+    """The kernel keeps a row's reference exponent until the row's probabilities outgrow it.  Scores that climb
+    along the sequence by several binades a token force that re-centring tile after tile; a single spike in
+    mid-sequence forces it once, by 100 binades; falling scores never do.  Every row against the oracle."""
+    shp = W.Shape("t", 0, hq, hkv, d, 1)
+    lens = np.array([700, 431, 520, 300], dtype=np.int32)
+    ql = np.array([700, 200, 520, 300], dtype=np.int32)
+    w = W.build(shp, lens, seed=21, cfg=86)
+    q, ql, offs = prefill_inputs(w, ql, seed=22)
+    u = np.zeros(d, dtype=np.float64)
+    u[: d // 2] = 1.0                                   # |u|^2 = d / 2, so q . k = gain * d / 2 for q = u
+    per_unit = (d / 2) / np.sqrt(d) * np.log2(np.e)     # binades of score per unit of gain
+    ramps = [np.arange(700) * (2.5 / per_unit),          # +2.5 binades a token: 80 a tile
+             np.where(np.arange(431) == 300, 100.0 / per_unit, 0.0),   # one key 100 binades above the rest
+             -np.arange(520) * (1.0 / per_unit),         # falling: the first tile's reference stays
+             np.sin(np.arange(300) * 0.05) * (40.0 / per_unit)]        # rising and falling by 40 binades
+    for b, g in enumerate(ramps):
+        _set_keys_along(w, b, u, g)
+        q[offs[b]:offs[b] + ql[b]] = W.f32_to_bf16_bits(np.broadcast_to(u, (int(ql[b]), hq, d)).astype(np.float32))
+    ref = jo.prefill_attention(q, w.k_pages, w.v_pages, w.block_table, w.seq_lens, ql, offs)
+    got = run_prefill(torch_cuda, w, q, ql, offs)
+    check(got, ref, ql, offs)
+
+
 def test_long_prefill_spans_many_query_blocks(torch_cuda, jo):
     shp = W.Shape("t", 0, 32, 8, 128, 1)
     lens = np.array([3000, 1111, 4097], dtype=np.int32)
