@@ -2,7 +2,7 @@
 // multi-turn rollout): the last q_lens[b] tokens of request b attend to everything before them and to
 // each other causally.  Unlike decode this is bound by the matrix cores, not by HBM.
 //
-// One block of kNW waves serves one (request, kv head, block of query tokens); two blocks share a
+// One block of kNW waves serves one (request, kv head, block of query tokens); two blocks (three at head_dim 64) share a
 // compute unit, so that one's matrix work runs while the other's softmax arithmetic does.  Each wave
 // holds one tile of 32 query rows in registers (row r of a request's kv head is query head r % G of new
 // token r / G, packed densely whatever G is), and all waves sweep the same K/V pages, which the block stages in
@@ -148,7 +148,7 @@ template <int T>
 struct Tensor { static constexpr int value = T; };
 
 template <int D>
-__global__ __launch_bounds__(kNW * 64, 2) void prefill_kernel(Params p, PrefillArgs a)
+__global__ __launch_bounds__(kNW * 64, D == 64 ? 3 : 2) void prefill_kernel(Params p, PrefillArgs a)
 {
     constexpr int kSP = 4;   // pages (16 keys each) per ring stage: one barrier and one softmax update per 64 keys
     constexpr int kRowBytes = D * 2;
