@@ -2,21 +2,21 @@
 // multi-turn rollout): the last q_lens[b] tokens of request b attend to everything before them and to
 // each other causally.  Unlike decode this is bound by the matrix cores, not by HBM.
 //
-// One block of kNW waves serves one (request, kv head, block of query tokens); two blocks (three at head_dim 64) share a
-// compute unit, so that one's matrix work runs while the other's softmax arithmetic does.  Each wave
-// holds one tile of 32 query rows in registers (row r of a request's kv head is query head r % G of new
-// token r / G, packed densely whatever G is), and all waves sweep the same K/V pages, which the block stages in
-// shared LDS rings of 64-key stages with direct loads (each wave issues its share of a stage; one
-// barrier and one softmax update per stage).  The block table reaches LDS the same way, a window of
-// 64 page ids at a time, so no round waits for a table read.  Per stage, with 32x32 matrix tiles
-// (v_mfma_f32_32x32x16_bf16: half as many matrix instructions per FLOP as 16x16 tiles, and a SIMD issues
-// matrix and vector instructions through one port, which is what bounds this kernel):
-//   S^T[key][row]  = K . Q^T, two tiles of 32 keys; a lane ends up with 16 keys of one query row per
-//                    tile, its partner lane (l ^ 32) with the other 16,
-//   online softmax in the exp2 domain: one row per lane, one exchange with the partner per stage,
+// One block of kNW waves serves one (request, kv head, block of query tokens); two blocks (three at
+// head_dim 64) share a compute unit.  Each wave holds one tile of 32 query rows in registers (row r of a
+// request's kv head is query head r % G of new token r / G, packed densely whatever G is), and all waves
+// sweep the same K/V pages, which the block stages in shared LDS rings of 64-key stages with direct loads
+// (every wave loads one page of a stage; one barrier per stage).  The block table reaches LDS the same
+// way, a window of 64 page ids at a time, so no round waits for a table read.  Per 32-key tile, with 32x32
+// matrix tiles (v_mfma_f32_32x32x16_bf16, one query row per lane):
+//   S^T[key][row]  = K . Q^T; a lane ends up with 16 keys of its query row, its partner lane (l ^ 32)
+//                    with the other 16,
+//   online softmax in the exp2 domain against the reference exponent the row already has; row maxima,
+//                    a new reference and rescaled accumulators only when a row has outgrown it,
 //   O^T[d][row]   += V^T . P^T, one page (16 keys) per instruction: the 8 keys a lane holds of a page are
 //                    its k-group of the contraction, so P needs no shuffle; P as bf16 head + bf16 remainder,
 //                    V read transposed from LDS.
+// The three are software-pipelined over consecutive tiles and their instructions ordered by hand.
 // Keys after a row's own position are excluded by selection (only in the rounds that reach the
 // diagonal); pages wholly above the block's last position are never fetched.  Requests are dispatched
 // by decreasing work (a small ranking kernel runs first), the query blocks of a request heaviest first.
