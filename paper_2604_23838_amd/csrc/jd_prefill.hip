@@ -170,7 +170,12 @@ __global__ __launch_bounds__(kNW * 64, D == 64 ? 3 : 2) void prefill_kernel(Para
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int bkv = blockIdx.x / a.nqb;
+    // Blocks go to the chip's eight dies in turn (block i to die i % 8), each die with an L2 of its own.  When the
+    // kv heads come in eights, die d takes the kv heads congruent to d of every request: all query blocks of a
+    // (request, kv head) then read its K/V pages through one L2, and every die gets the same share of every request.
+    const bool by_die = p.Hkv % 8 == 0;
+    const int lin = by_die ? static_cast<int>(blockIdx.x / 8) : static_cast<int>(blockIdx.x);
+    const int bkv = by_die ? (lin / a.nqb) * 8 + static_cast<int>(blockIdx.x % 8) : lin / a.nqb;
     const int b = min(max(uniform_load(a.order + bkv / p.Hkv), 0), p.B - 1), kv = bkv % p.Hkv;
     const int L0 = uniform_load(p.seq_lens + b);
     int n = uniform_load(a.q_lens + b);
@@ -180,7 +185,7 @@ __global__ __launch_bounds__(kNW * 64, D == 64 ? 3 : 2) void prefill_kernel(Para
     const int c = L - n;                   // tokens of context in front of the new ones
     // query rows of the request: row r is head r % G of new token r / G (no padding of the group)
     const int nrows = n * p.G;
-    const int qb = a.nqb - 1 - static_cast<int>(blockIdx.x % a.nqb);   // heaviest query block first
+    const int qb = a.nqb - 1 - lin % a.nqb;   // heaviest query block first
     const int r0 = qb * kPrefillBlockRows;
     if (r0 >= nrows) return;
     const int qoff = uniform_load(a.q_offsets + b);
