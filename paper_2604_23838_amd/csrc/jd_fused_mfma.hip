@@ -48,6 +48,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) char lds_char;
 
@@ -494,10 +495,7 @@ struct Wave {
             const unsigned o = rec + (qh * D + 4 * tg) * 4u;
 #pragma unroll
             for (int jd = 0; jd < D / 16; ++jd) shared_store4(o + 64 * jd, acc[jd]);
-            if (tg == 0) {
-                shared_store1(rec + (p.G * D + qh) * 4u, m);
-                shared_store1(rec + (p.G * D + p.G + qh) * 4u, lt);
-            }
+            if (tg == 0) shared_store2(rec + (p.G * D + 2 * qh) * 4u, m, lt);   // (m, l) of a row side by side
         }
     }
 
@@ -514,6 +512,15 @@ struct Wave {
     __device__ inline void shared_store1(unsigned off, float v) const
     {
         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), records, off, 0, kDeviceCoherent);
+    }
+    __device__ inline void shared_store2(unsigned off, float a, float b) const
+    {
+        __builtin_amdgcn_raw_buffer_store_b64(u32x2{__builtin_bit_cast(unsigned, a), __builtin_bit_cast(unsigned, b)}, records, off, 0,
+                                              kDeviceCoherent);
+    }
+    __device__ inline f32x2 shared_load2(unsigned off) const
+    {
+        return __builtin_bit_cast(f32x2, __builtin_amdgcn_raw_buffer_load_b64(records, off, 0, kDeviceCoherent));
     }
     __device__ inline f32x4 shared_load4(unsigned off) const
     {
@@ -545,11 +552,13 @@ struct Wave {
 
     // Log-sum-exp merge of the pieces of one stream, by one wave.  The G*D accumulator floats of a
     // record are contiguous; lane j owns the float4 groups j, j+64, ... of them (each group lies in
-    // one query row).  Pieces are fetched a batch at a time so that their loads overlap.
+    // one query row; a wave's load of one group per lane is contiguous).  Pieces are fetched a batch at a
+    // time so that their loads overlap: per piece and group one load of the group and one of its row's
+    // (m, l) pair, as many pieces as the wave may have in flight; pieces past the last are not fetched.
     __device__ inline void merge(int bkv, int a, int w0, int w1)
     {
-        constexpr int K = 2 * QKB;   // float4 groups per lane: G*D*2 <= QKB KiB, so G*D/4 <= 128*QKB groups
-        constexpr int PB = 32 / K;   // pieces per batch
+        constexpr int K = 2 * QKB;           // float4 groups per lane: G*D*2 <= QKB KiB, so G*D/4 <= 128*QKB groups
+        constexpr int PB = 60 / (2 * K);     // pieces per batch: at most 63 loads of a wave are counted in flight
         const int G = p.G;
         const int groups = G * D / 4;
         const unsigned rec_bytes = record_floats(G, D) * 4u;
@@ -566,29 +575,30 @@ struct Wave {
 #pragma unroll
         for (int k = 0; k < K; ++k) { M[k] = -__builtin_inff(); den[k] = 0.f; num[k] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 
-        for (int w = w0; w <= w1; w += PB) {
-            float mm[PB][K], ll[PB][K];
-            f32x4 aa[PB][K];
+        struct Batch { f32x2 ml[PB][K]; f32x4 aa[PB][K]; };
+        auto fetch = [&](int w, Batch& t) __attribute__((always_inline)) {
 #pragma unroll
             for (int i = 0; i < PB; ++i) {
-                const int wi = min(w + i, w1);  // the tail of a batch re-reads the last piece and is ignored below
+                const int wi = w + i;
+                if (wi > w1) continue;
                 const int slot = (a < wi * span) ? 0 : 1;
                 const unsigned rec = static_cast<unsigned>((wi * p.wg + rec_member) * 2 + slot) * rec_bytes;
 #pragma unroll
                 for (int k = 0; k < K; ++k) {
                     if (idx[k] < 0) continue;
-                    mm[i][k] = shared_load1(rec + (G * D + qrow[k]) * 4u);
-                    ll[i][k] = shared_load1(rec + (G * D + G + qrow[k]) * 4u);
-                    aa[i][k] = shared_load4(rec + idx[k] * 16u);
+                    t.ml[i][k] = shared_load2(rec + (G * D + 2 * qrow[k]) * 4u);
+                    t.aa[i][k] = shared_load4(rec + idx[k] * 16u);
                 }
             }
+        };
+        auto fold = [&](int w, const Batch& t) __attribute__((always_inline)) {
 #pragma unroll
             for (int k = 0; k < K; ++k) {
                 if (idx[k] < 0) continue;
                 float mb = M[k];
 #pragma unroll
                 for (int i = 0; i < PB; ++i)
-                    if (w + i <= w1) mb = fmaxf(mb, mm[i][k]);
+                    if (w + i <= w1) mb = fmaxf(mb, t.ml[i][k][0]);
                 const float c_old = __builtin_amdgcn_exp2f(M[k] - mb);
                 M[k] = mb;
                 den[k] *= c_old;
@@ -597,12 +607,17 @@ struct Wave {
 #pragma unroll
                 for (int i = 0; i < PB; ++i) {
                     if (w + i > w1) continue;
-                    const float c = __builtin_amdgcn_exp2f(mm[i][k] - mb);
-                    den[k] = fmaf(c, ll[i][k], den[k]);
+                    const float c = __builtin_amdgcn_exp2f(t.ml[i][k][0] - mb);
+                    den[k] = fmaf(c, t.ml[i][k][1], den[k]);
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) num[k][r] = fmaf(c, aa[i][k][r], num[k][r]);
+                    for (int r = 0; r < 4; ++r) num[k][r] = fmaf(c, t.aa[i][k][r], num[k][r]);
                 }
             }
+        };
+        for (int w = w0; w <= w1; w += PB) {
+            Batch t;
+            fetch(w, t);
+            fold(w, t);
         }
         const int b = bkv / p.Hkv, kv = bkv % p.Hkv;
         float* o = p.out + (static_cast<size_t>(b) * p.Hq + kv * G) * D;  // the group's rows are contiguous, like the record's
