@@ -116,7 +116,7 @@ void fill_params(jd::Params& p, char* ws, const Layout& lay, const jd_config& c,
     p.B = c.batch; p.Hq = c.num_q_heads; p.Hkv = c.num_kv_heads;
     p.G = p.Hq / p.Hkv; p.D = c.head_dim; p.maxp = c.max_pages_per_seq; p.NP = c.num_pages;
     p.slots = slots;
-    p.wg = jd::mfma_group_waves(p.Hkv);
+    p.wg = jd::mfma_group_waves(p.Hkv, slots);
     const double scale = c.softmax_scale > 0.f ? static_cast<double>(c.softmax_scale) : 1.0 / std::sqrt(static_cast<double>(p.D));
     p.scale_log2e = static_cast<float>(scale * 1.4426950408889634);
 }

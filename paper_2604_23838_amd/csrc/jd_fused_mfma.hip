@@ -969,11 +969,13 @@ hipError_t launch(const Params& p, hipStream_t stream, int partition_only)
 int mfma_waves_per_cu() { return kWaves; }
 int mfma_waves_per_block() { return kWaves; }
 
-// Waves per group: the largest power of two that divides the kv-head count and fits a block.
-int mfma_group_waves(int num_kv_heads)
+// Waves per group: the largest power of two, at most 8, that divides the kv-head count and the wave slots
+// (with 8 kv heads every wave of a group serves one head, and a sequence is cut into half as many pieces
+// as with two heads a wave).
+int mfma_group_waves(int num_kv_heads, int slots)
 {
     int wg = 1;
-    while (wg * 2 <= kWaves && num_kv_heads % (wg * 2) == 0) wg *= 2;
+    while (wg * 2 <= 2 * kWaves && num_kv_heads % (wg * 2) == 0 && slots % (wg * 2) == 0) wg *= 2;
     return wg;
 }
 

@@ -66,7 +66,7 @@ hipError_t launch_partition(const Params& p, hipStream_t stream);
 hipError_t launch_partial_vector(const Params& p, hipStream_t stream);
 hipError_t launch_fused_mfma(const Params& p, hipStream_t stream, int partition_only);
 int mfma_max_batch();
-int mfma_group_waves(int num_kv_heads);
+int mfma_group_waves(int num_kv_heads, int slots);
 hipError_t launch_combine(const Params& p, hipStream_t stream);
 hipError_t launch_append_kv(const Params& p, const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pages,
                             uint16_t* v_pages, int32_t* seq_lens, const int32_t* active, hipStream_t stream);

@@ -195,7 +195,7 @@ def walk_partition(lens, hkv, maxp, hdr, wave_start):
     return n, seen, owned
 
 
-@pytest.mark.parametrize("hkv,d", [(8, 128), (2, 64), (5, 64), (1, 128)])   # wave groups of 4, 2, 1 and 1
+@pytest.mark.parametrize("hkv,d", [(8, 128), (2, 64), (5, 64), (1, 128)])   # wave groups of 8 (4 on budgets that 8 does not divide), 2, 1 and 1
 def test_partition_owns_every_page_exactly_once(torch_cuda, hkv, d):
     """The work partition pinned by validity on what the library itself returns: every (request, kv head, page)
     unit is owned by exactly one wave, every active group owns `span` units and the last one the remainder."""
@@ -214,7 +214,10 @@ def test_partition_owns_every_page_exactly_once(torch_cuda, hkv, d):
             hdr, ws, cum = op.partition(tl)
             units, span, active, slots, wg = hdr[:5]
             assert slots == jb.jd_wave_slots(op.handle) and slots % wg == 0
-            assert wg == min(4, hkv & -hkv)
+            want = 1                                           # the largest power of two up to 8 dividing heads and slots
+            while want < 8 and hkv % (2 * want) == 0 and slots % (2 * want) == 0:
+                want *= 2
+            assert wg == want
             n, seen, owned = walk_partition(lens, hkv, maxp, hdr, ws)
             assert units == int(n.sum()) * (hkv // wg)
             assert cum == np.concatenate([[0], np.cumsum(n)]).tolist()

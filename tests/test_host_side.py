@@ -90,7 +90,7 @@ def test_schedule_is_valid():
         assert (active - 1) * span < units <= active * span or (units == 0 and active == 0), (units, slots)
 
 
-@pytest.mark.parametrize("wg,hkv", [(1, 2), (2, 2), (4, 8), (1, 5)])
+@pytest.mark.parametrize("wg,hkv", [(1, 2), (2, 2), (4, 8), (8, 8), (1, 5)])
 def test_reference_partition_covers_every_page_once(wg, hkv):
     rng = np.random.default_rng(1)
     lens = np.floor(rng.lognormal(np.log(700.0), 1.2, size=300)).astype(int).clip(0, 9000)
