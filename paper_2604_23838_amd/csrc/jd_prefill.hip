@@ -150,7 +150,7 @@ struct Tensor { static constexpr int value = T; };
 template <int D>
 __global__ __launch_bounds__(kNW * 64, D == 64 ? 3 : 2) void prefill_kernel(Params p, PrefillArgs a)
 {
-    constexpr int kSP = 4;   // pages (16 keys each) per ring stage: one barrier and one softmax update per 64 keys
+    constexpr int kSP = 4;   // pages (16 keys each) per ring stage: one barrier per 64 keys, two 32-key tiles
     constexpr int kRowBytes = D * 2;
     constexpr int kPageBytes = kPage * kRowBytes;
     constexpr int kStageBytes = kSP * kPageBytes;             // one tensor's share of a stage
