@@ -51,7 +51,7 @@ def check(got, ref, q_lens, offs):
         assert ma <= ABS_TOL and mr <= REL_TOL, (ma, mr)
 
 
-SHAPES = [(8, 2, 64), (32, 8, 128), (14, 2, 64), (64, 8, 128), (16, 1, 64), (12, 4, 128), (4, 4, 128)]
+SHAPES = [(8, 2, 64), (32, 8, 128), (14, 2, 64), (64, 8, 128), (16, 1, 64), (12, 4, 128), (4, 4, 128), (16, 16, 64), (48, 24, 128)]
 
 
 @pytest.mark.parametrize("hq,hkv,d", SHAPES)
