@@ -844,7 +844,12 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
     const int active = (units + span - 1) / span;   // groups that own at least one unit
 
     const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * kWaves + wave_in_block);
+    // Blocks go to the chip's eight dies in turn (block i to die i % 8).  Waves are numbered die by die, so that
+    // consecutive spans of the work line, and with them the pieces of a sequence, sit on one die.
+    const int nblocks = static_cast<int>(gridDim.x);
+    const int block = nblocks % 8 == 0 ? static_cast<int>(blockIdx.x % 8) * (nblocks / 8) + static_cast<int>(blockIdx.x / 8)
+                                       : static_cast<int>(blockIdx.x);
+    const int wave = __builtin_amdgcn_readfirstlane(block * kWaves + wave_in_block);
     const int group = wave / p.wg, member = wave % p.wg;
     int sr = 0, sb = 0, skv = 0, spg = 0;
     if (group < active) {
