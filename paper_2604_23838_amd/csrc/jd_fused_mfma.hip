@@ -87,6 +87,14 @@ __device__ inline void dma16(unsigned lds_addr, unsigned lane_off, const void* b
                  :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
 }
 
+// The same for a partial record that another compute unit has written: a device-coherent load (sc1), which
+// bypasses the cache levels that are not coherent between dies.
+__device__ inline void dma16_shared(unsigned lds_addr, unsigned lane_off, const void* base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 sc1"
+                 :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
+}
+
 // The direct loads of one tensor's page, or of both tensors' pages when they fit the instruction's offset range:
 // one LDS base in m0, the j-th load 1 KiB further on.  The instruction offset moves the global address and
 // the LDS address alike, so the per-lane source offsets come with j KiB taken off (see init_lane_tables).
@@ -500,35 +508,19 @@ struct Wave {
     }
 
     // Records are shared between compute units that sit behind different L2 caches.  They are
-    // written and read with device-coherent accesses (sc1: write-through stores, loads that
-    // bypass the non-coherent cache levels), so that no cache-wide write-back or invalidate is
-    // ever needed.  `off` is a byte offset into the record area; the buffer descriptor bounds
-    // every access to that area.
+    // written and read with device-coherent accesses (sc1: write-through stores here, loads that
+    // bypass the non-coherent cache levels in the merge), so that no cache-wide write-back or
+    // invalidate is ever needed.  `off` is a byte offset into the record area; the buffer
+    // descriptor bounds every store to that area.
     static constexpr int kDeviceCoherent = 16;  // cache-policy bit sc1
     __device__ inline void shared_store4(unsigned off, f32x4 v) const
     {
         __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), records, off, 0, kDeviceCoherent);
     }
-    __device__ inline void shared_store1(unsigned off, float v) const
-    {
-        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), records, off, 0, kDeviceCoherent);
-    }
     __device__ inline void shared_store2(unsigned off, float a, float b) const
     {
         __builtin_amdgcn_raw_buffer_store_b64(u32x2{__builtin_bit_cast(unsigned, a), __builtin_bit_cast(unsigned, b)}, records, off, 0,
                                               kDeviceCoherent);
-    }
-    __device__ inline f32x2 shared_load2(unsigned off) const
-    {
-        return __builtin_bit_cast(f32x2, __builtin_amdgcn_raw_buffer_load_b64(records, off, 0, kDeviceCoherent));
-    }
-    __device__ inline f32x4 shared_load4(unsigned off) const
-    {
-        return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(records, off, 0, kDeviceCoherent));
-    }
-    __device__ inline float shared_load1(unsigned off) const
-    {
-        return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(records, off, 0, kDeviceCoherent));
     }
 
     // ---- epilogue: arrival counters and last-arriver merge -------------------------------------
@@ -552,16 +544,21 @@ struct Wave {
 
     // Log-sum-exp merge of the pieces of one stream, by one wave.  The G*D accumulator floats of a
     // record are contiguous; lane j owns the float4 groups j, j+64, ... of them (each group lies in
-    // one query row; a wave's load of one group per lane is contiguous).  Pieces are fetched a batch at a
-    // time so that their loads overlap: per piece and group one load of the group and one of its row's
-    // (m, l) pair, as many pieces as the wave may have in flight; pieces past the last are not fetched.
+    // one query row).  The wave's page ring is empty by now and takes the records: a batch of pieces is
+    // copied into it whole by direct loads, 16 bytes a lane and load, as many pieces as fit the ring
+    // and the counter of loads in flight, so that all of them overlap; then the pieces are folded in one
+    // after the other from LDS.  Both loops are short and rolled: a merge runs once or twice per wave,
+    // mostly on instructions that no cache holds any more, so every instruction it executes is also one
+    // that has to be fetched first.
     __device__ inline void merge(int bkv, int a, int w0, int w1)
     {
         constexpr int K = 2 * QKB;           // float4 groups per lane: G*D*2 <= QKB KiB, so G*D/4 <= 128*QKB groups
-        constexpr int PB = 60 / (2 * K);     // pieces per batch: at most 63 loads of a wave are counted in flight
+        constexpr int NL = K + 1;            // 1 KiB loads per record: its G*D*4 <= K KiB, its (m, l) pairs another 8*G bytes
         const int G = p.G;
         const int groups = G * D / 4;
-        const unsigned rec_bytes = record_floats(G, D) * 4u;
+        const unsigned rec_bytes = record_floats(G, D) * 4u;   // a whole number of 16-byte units
+        const unsigned rec_copy = rec_bytes;
+        const int fit = min(static_cast<int>(Geo::kWaveBytes / rec_copy), 60 / NL);   // pieces per batch
         const int rec_member = (bkv % p.Hkv) % p.wg;  // the piece of group g sits in the records of wave g*wg + member
         int idx[K], qrow[K];
 #pragma unroll
@@ -575,49 +572,40 @@ struct Wave {
 #pragma unroll
         for (int k = 0; k < K; ++k) { M[k] = -__builtin_inff(); den[k] = 0.f; num[k] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 
-        struct Batch { f32x2 ml[PB][K]; f32x4 aa[PB][K]; };
-        auto fetch = [&](int w, Batch& t) __attribute__((always_inline)) {
-#pragma unroll
-            for (int i = 0; i < PB; ++i) {
+        for (int w = w0; w <= w1; w += fit) {
+            const int nb = min(fit, w1 - w + 1);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the LDS reads of the batch before have returned
+#pragma unroll 1
+            for (int i = 0; i < nb; ++i) {
                 const int wi = w + i;
-                if (wi > w1) continue;
                 const int slot = (a < wi * span) ? 0 : 1;
                 const unsigned rec = static_cast<unsigned>((wi * p.wg + rec_member) * 2 + slot) * rec_bytes;
+                const char* src = scalar_ptr(reinterpret_cast<const char*>(p.partials) + rec);
+                const unsigned dst = lds_wave + static_cast<unsigned>(i) * rec_copy;
+#pragma unroll
+                for (int j = 0; j < NL; ++j) {
+                    const unsigned off = j * 1024u + lane * 16u;
+                    if (off < rec_copy) dma16_shared(dst + j * 1024u, off, src);
+                }
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll 1
+            for (int i = 0; i < nb; ++i) {
+                const lds_char* rec = lds_ptr + static_cast<unsigned>(i) * rec_copy;
 #pragma unroll
                 for (int k = 0; k < K; ++k) {
                     if (idx[k] < 0) continue;
-                    t.ml[i][k] = shared_load2(rec + (G * D + 2 * qrow[k]) * 4u);
-                    t.aa[i][k] = shared_load4(rec + idx[k] * 16u);
+                    const f32x2 ml = *reinterpret_cast<const __attribute__((address_space(3))) f32x2*>(rec + (G * D + 2 * qrow[k]) * 4);
+                    const f32x4 aa = *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(rec + idx[k] * 16);
+                    const float mb = fmaxf(M[k], ml[0]);
+                    const float c_old = __builtin_amdgcn_exp2f(M[k] - mb);
+                    const float c = __builtin_amdgcn_exp2f(ml[0] - mb);
+                    M[k] = mb;
+                    den[k] = fmaf(c, ml[1], den[k] * c_old);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) num[k][r] = fmaf(c, aa[r], num[k][r] * c_old);
                 }
             }
-        };
-        auto fold = [&](int w, const Batch& t) __attribute__((always_inline)) {
-#pragma unroll
-            for (int k = 0; k < K; ++k) {
-                if (idx[k] < 0) continue;
-                float mb = M[k];
-#pragma unroll
-                for (int i = 0; i < PB; ++i)
-                    if (w + i <= w1) mb = fmaxf(mb, t.ml[i][k][0]);
-                const float c_old = __builtin_amdgcn_exp2f(M[k] - mb);
-                M[k] = mb;
-                den[k] *= c_old;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) num[k][r] *= c_old;
-#pragma unroll
-                for (int i = 0; i < PB; ++i) {
-                    if (w + i > w1) continue;
-                    const float c = __builtin_amdgcn_exp2f(t.ml[i][k][0] - mb);
-                    den[k] = fmaf(c, t.ml[i][k][1], den[k]);
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) num[k][r] = fmaf(c, t.aa[i][k][r], num[k][r]);
-                }
-            }
-        };
-        for (int w = w0; w <= w1; w += PB) {
-            Batch t;
-            fetch(w, t);
-            fold(w, t);
         }
         const int b = bkv / p.Hkv, kv = bkv % p.Hkv;
         float* o = p.out + (static_cast<size_t>(b) * p.Hq + kv * G) * D;  // the group's rows are contiguous, like the record's

@@ -45,7 +45,7 @@ struct Params {
     int32_t* req;               // [B] request id of the r-th non-empty request
     int32_t* order;             // [B] requests by decreasing prefill work
     int32_t* wave_start;        // [slots * 4] {r, kv, page, 0}
-    float* partials;            // [slots * 2] records of G*(D+2) floats: acc[G][D], m[G], l[G]
+    float* partials;            // [slots * 2] records, record_floats(G, D) floats apart: G*D accumulator values, then m and l of the G rows
     int32_t* counters;          // [B * Hkv] arrival counters of the fused kernel (zero between calls)
     int32_t B, Hq, Hkv, G, D, maxp, NP, slots;
     int32_t wg;                 // waves per group in the fused kernel (divides Hkv and slots)
@@ -59,7 +59,9 @@ inline __host__ __device__ int span_for(int units, int slots)
     return span < kMinSpan ? kMinSpan : span;
 }
 
-inline __host__ __device__ int record_floats(int G, int D) { return G * (D + 2); }
+// Floats from one partial record to the next: G*D accumulator values, then G (m, l) pairs, rounded up to a whole
+// number of 16-byte units (the merge copies records 16 bytes a lane).
+inline __host__ __device__ int record_floats(int G, int D) { return (G * (D + 2) + 3) & ~3; }
 
 // Launchers (each enqueues on `stream` and returns hipGetLastError()).
 hipError_t launch_partition(const Params& p, hipStream_t stream);
