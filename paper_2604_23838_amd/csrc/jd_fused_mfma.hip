@@ -726,16 +726,20 @@ struct Wave {
         // this wave owes at most one merge when it ends (for the stream its span ends in) instead of two.
         const int first_end = first_a + first_n - u0;   // stages the first stream takes in this span, if it ends inside
         bool announced = false;
+        // stages after which the piece may be announced (never reached when there is nothing to announce)
+        const int stop = (first_partial && first_end < total) ? first_end + NS - 1 : total;
         int base = 0;
-        if (first_partial && first_end < total) {
-            const int stop = first_end + NS - 1;
-            for (; base + kSteady < total && base < stop; base += NS) steady_round();
-            if (base >= stop) {
+        for (; base + kSteady < total; base += NS) {   // one copy of the steady round in the kernel's code
+            if (base >= stop && !announced) {
                 if (lane == 0) (void)__hip_atomic_fetch_add(p.counters + first_bkv, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 announced = true;
             }
+            steady_round();
         }
-        for (; base + kSteady < total; base += NS) steady_round();
+        if (base >= stop && !announced) {
+            if (lane == 0) (void)__hip_atomic_fetch_add(p.counters + first_bkv, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            announced = true;
+        }
         for (; base < total; base += NS) round_stage<0>(base, total);
 
         const bool last_partial = cur.last_a != first_a && cur.last_a + cur.last_n > u1;
