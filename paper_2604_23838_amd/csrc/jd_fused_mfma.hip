@@ -560,12 +560,15 @@ struct Wave {
         const unsigned rec_copy = rec_bytes;
         const int fit = min(static_cast<int>(Geo::kWaveBytes / rec_copy), 60 / NL);   // pieces per batch
         const int rec_member = (bkv % p.Hkv) % p.wg;  // the piece of group g sits in the records of wave g*wg + member
-        int idx[K], qrow[K];
+        // A lane without a k-th group folds group 0 in its place and stores nothing for it: the loop below
+        // then has no divergent parts, and the reads of a lane's groups are issued together.
+        int idx[K], grp[K], qrow[K];
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             idx[k] = lane + 64 * k;
             if (idx[k] >= groups) idx[k] = -1;
-            qrow[k] = idx[k] < 0 ? 0 : idx[k] * 4 / D;
+            grp[k] = idx[k] < 0 ? 0 : idx[k];
+            qrow[k] = grp[k] * 4 / D;
         }
         float M[K], den[K];
         f32x4 num[K];
@@ -594,9 +597,8 @@ struct Wave {
                 const lds_char* rec = lds_ptr + static_cast<unsigned>(i) * rec_copy;
 #pragma unroll
                 for (int k = 0; k < K; ++k) {
-                    if (idx[k] < 0) continue;
                     const f32x2 ml = *reinterpret_cast<const __attribute__((address_space(3))) f32x2*>(rec + (G * D + 2 * qrow[k]) * 4);
-                    const f32x4 aa = *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(rec + idx[k] * 16);
+                    const f32x4 aa = *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(rec + grp[k] * 16);
                     const float mb = fmaxf(M[k], ml[0]);
                     const float c_old = __builtin_amdgcn_exp2f(M[k] - mb);
                     const float c = __builtin_amdgcn_exp2f(ml[0] - mb);
