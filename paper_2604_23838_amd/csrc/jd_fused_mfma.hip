@@ -547,9 +547,12 @@ struct Wave {
     // one query row).  The wave's page ring is empty by now and takes the records: a batch of pieces is
     // copied into it whole by direct loads, 16 bytes a lane and load, as many pieces as fit the ring
     // and the counter of loads in flight, so that all of them overlap; then the pieces are folded in one
-    // after the other from LDS.  Both loops are short and rolled: a merge runs once or twice per wave,
-    // mostly on instructions that no cache holds any more, so every instruction it executes is also one
-    // that has to be fetched first.
+    // after the other from LDS.  The direct loads are inline assembly with one explicit wait behind
+    // them: compiler-visible loads into registers inside the loop over batches get a full wait in front
+    // of each of them from the compiler (their registers may still be the target of a load of the trip
+    // before), which turns a merge of 13 pieces into 26 round trips to memory, one after the other.
+    // The loops are rolled and short: a wave that is alone on its SIMD issues one instruction every
+    // four cycles, so at the end of a step the length of this code in instructions is its time.
     __device__ inline void merge(int bkv, int a, int w0, int w1)
     {
         constexpr int K = 2 * QKB;           // float4 groups per lane: G*D*2 <= QKB KiB, so G*D/4 <= 128*QKB groups
@@ -676,8 +679,10 @@ struct Wave {
     // Two such rounds at once where the ring is deep enough to spare a slot: both pages have landed, and if they are
     // full pages from the middle of one segment (nothing begins or ends in either) they are consumed as a pair.
     // Two units are then kept planned (nx, nx2), so that each block-table entry is still requested a pair ahead
-    // of its use.
-    static constexpr bool kPairs = NS >= 6 && NS % 2 == 0;
+    // of its use.  Not with a 2 KiB query slot (64-wide heads, more than 8 query heads per kv head): in that
+    // instantiation the compiler takes the wave-uniform loads of lengths and page ids in the loop through the
+    // vector path, with a full wait behind each of them, which drains the ring (4.2 against 6.0 TB/s measured).
+    static constexpr bool kPairs = NS >= 6 && NS % 2 == 0 && QKB == 1;
     template <int S>
     __device__ inline void steady_pair()
     {
