@@ -80,10 +80,10 @@ def test_one_very_long_sequence_cut_into_many_pieces(torch_cuda, jo):
     check(run_gpu(torch_cuda, arrays(w)), ref, f"very long")
 
 
-@pytest.mark.parametrize("hq,hkv,d", [(14, 2, 64), (64, 4, 128), (8, 8, 128), (6, 6, 64), (16, 1, 128)])
+@pytest.mark.parametrize("hq,hkv,d", [(14, 2, 64), (64, 4, 128), (8, 8, 128), (6, 6, 64), (16, 1, 128), (16, 1, 64), (24, 2, 64)])
 def test_long_sequences_on_every_record_size(torch_cuda, jo, hq, hkv, d):
-    # the merge of many pieces with 1, 2 and 4 KiB query slots (its batch size depends on it), group sizes 1 to 16
-    # and wave groups of 1, 2 and 4
+    # the merge of many pieces with 1, 2 and 4 KiB query slots (its batch size depends on it), group sizes 1 to 16,
+    # wave groups of 1, 2 and 4, and every instantiation of the kernel (64-wide heads with a 2 KiB slot included)
     lens = np.array([7, 50000, 0, 33000], dtype=np.int32)
     w = W.build(W.Shape("t", 0, hq, hkv, d, 1), lens, seed=24, cfg=90)
     ref = jo.decode_attention(*arrays(w))
