@@ -43,10 +43,11 @@ Layout make_layout(const jd_config& c, int slots)
     l.req = off; off = align_up(off + sizeof(int32_t) * static_cast<size_t>(c.batch), 256);
     l.order = off; off = align_up(off + sizeof(int32_t) * static_cast<size_t>(c.batch), 256);
     l.wave_start = off; off = align_up(off + sizeof(int32_t) * 4 * static_cast<size_t>(slots), 256);
-    l.counters = off; off = align_up(off + sizeof(int32_t) * static_cast<size_t>(c.batch) * c.num_kv_heads, 256);
+    l.counters = off;
+    off = align_up(off + sizeof(int32_t) * (static_cast<size_t>(c.batch) * c.num_kv_heads + jd::cluster_records(slots)), 256);
     const int G = c.num_q_heads / c.num_kv_heads;
     l.partials = off;
-    off = align_up(off + sizeof(float) * 2 * static_cast<size_t>(slots) * jd::record_floats(G, c.head_dim), 256);
+    off = align_up(off + sizeof(float) * (2 * static_cast<size_t>(slots) + jd::cluster_records(slots)) * jd::record_floats(G, c.head_dim), 256);
     l.total = off;
     return l;
 }
@@ -303,7 +304,7 @@ jd_status jd_decode_attention_static(const jd_config* cfg, const void* q, const 
     p.seq_lens = seq_lens;
     p.out = out;
     // the array keeps the last call's contents, and that call may have had another configuration
-    const int n_counters = p.B * p.Hkv;
+    const int n_counters = p.B * p.Hkv + jd::cluster_records(p.slots);
     const int n_clear = n_counters > jd::kHeaderInts ? n_counters : jd::kHeaderInts;
     hipLaunchKernelGGL(static_clear_kernel, dim3((n_clear + 255) / 256), dim3(256), 0, s, p.header, p.counters, n_counters);
     e = hipGetLastError();

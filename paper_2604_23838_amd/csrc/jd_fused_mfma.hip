@@ -530,39 +530,80 @@ struct Wave {
     // an answer may have been the last to be counted, which only its own later look (add = 0) can find
     // out; that look may also come just before another wave, which counted last, resets the counter:
     // the stream is then merged twice, to the same bits.
+    //
+    // A stream of kFlatMergePieces pieces or more is merged in two levels, so that no single wave has to
+    // fold them all: the piece is counted in its cluster of kMergeCluster wave groups; the last one there
+    // merges the cluster's pieces into the cluster's record, waits for its stores and counts the cluster in the
+    // stream's counter; the last cluster merges the cluster records.  Every count at both levels is an add whose
+    // answer is awaited (pieces of such streams are never announced early), so each merge happens once.
+    static constexpr int kWholeStream = -1;
+    // more than kFlatMergePieces - 1 spans long: cut into kFlatMergePieces pieces at least, i.e. over two clusters or more
+    __device__ inline bool two_levels(int n) const { return n > (kFlatMergePieces - 1) * span; }
     __device__ inline void arrive(int bkv, int a, int n, int add)
     {
         const int w0 = a / span, w1 = (a + n - 1) / span;
-        int old = 0;
-        if (lane == 0) old = __hip_atomic_fetch_add(p.counters + bkv, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        old = __builtin_amdgcn_readfirstlane(old);
-        if (old + add != w1 - w0 + 1) return;
-        if (lane == 0) __hip_atomic_store(p.counters + bkv, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        asm volatile("" ::: "memory");  // the record loads below stay behind the counter read
-        merge(bkv, a, w0, w1);
+        // the only level: all pieces of the stream
+        int first = w0, last = w1, into = kWholeStream;
+        int* counter = p.counters + bkv;
+        if (two_levels(n)) {   // the first level of two: the cluster's part of the stream
+            const int c = group / kMergeCluster;
+            first = max(w0, c * kMergeCluster);
+            last = min(w1, c * kMergeCluster + kMergeCluster - 1);
+            into = cluster_record(c, w0);
+            counter = p.counters + p.B * p.Hkv + into;
+        }
+        bool from_clusters = false;
+#pragma unroll 1
+        for (;;) {
+            int old = 0;
+            if (lane == 0) old = __hip_atomic_fetch_add(counter, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            old = __builtin_amdgcn_readfirstlane(old);
+            if (old + add != last - first + 1) return;
+            if (lane == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            asm volatile("" ::: "memory");  // the record loads below stay behind the counter read
+            // the record of item i: of wave group i, the first of its wave's two if the piece began before that wave's
+            // span (a < i*span), the second otherwise; of cluster i, behind all of those, by the same rule (w0 < i*16)
+            merge(bkv, first, last, from_clusters ? 2 * p.slots : 0, from_clusters ? w0 : a, from_clusters ? kMergeCluster : span, into);
+            if (into == kWholeStream) return;
+            // second level: the cluster's record is complete in memory before the cluster is counted
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            first = w0 / kMergeCluster;
+            last = w1 / kMergeCluster;
+            counter = p.counters + bkv;
+            into = kWholeStream;
+            from_clusters = true;
+            add = 1;
+        }
     }
 
-    // Log-sum-exp merge of the pieces of one stream, by one wave.  The G*D accumulator floats of a
+    // Index of the record (and counter) of cluster c for the part of a stream that begins in wave group w0.
+    __device__ inline int cluster_record(int c, int w0) const
+    {
+        return ((c * p.wg + member) * 2 + (w0 < c * kMergeCluster ? 0 : 1));
+    }
+
+    // Log-sum-exp merge of records first..last of one stream, by one wave: its pieces (the records of the wave
+    // groups first..last) or the records of its clusters first..last (item i is record
+    // base + (i*wg + member)*2 + (start < i*stride ? 0 : 1)); the result goes to the output rows, normalised,
+    // or, as it is, into cluster record `into`.  The G*D accumulator floats of a
     // record are contiguous; lane j owns the float4 groups j, j+64, ... of them (each group lies in
-    // one query row).  The wave's page ring is empty by now and takes the records: a batch of pieces is
-    // copied into it whole by direct loads, 16 bytes a lane and load, as many pieces as fit the ring
-    // and the counter of loads in flight, so that all of them overlap; then the pieces are folded in one
+    // one query row).  The wave's page ring is empty by now and takes the records: a batch of them is
+    // copied into it whole by direct loads, 16 bytes a lane and load, as many records as fit the ring
+    // and the counter of loads in flight, so that all of them overlap; then they are folded in one
     // after the other from LDS.  The direct loads are inline assembly with one explicit wait behind
     // them: compiler-visible loads into registers inside the loop over batches get a full wait in front
     // of each of them from the compiler (their registers may still be the target of a load of the trip
     // before), which turns a merge of 13 pieces into 26 round trips to memory, one after the other.
     // The loops are rolled and short: a wave that is alone on its SIMD issues one instruction every
     // four cycles, so at the end of a step the length of this code in instructions is its time.
-    __device__ inline void merge(int bkv, int a, int w0, int w1)
+    __device__ inline void merge(int bkv, int first, int last, int base, int start, int stride, int into)
     {
         constexpr int K = 2 * QKB;           // float4 groups per lane: G*D*2 <= QKB KiB, so G*D/4 <= 128*QKB groups
         constexpr int NL = K + 1;            // 1 KiB loads per record: its G*D*4 <= K KiB, its (m, l) pairs another 8*G bytes
         const int G = p.G;
         const int groups = G * D / 4;
         const unsigned rec_bytes = record_floats(G, D) * 4u;   // a whole number of 16-byte units
-        const unsigned rec_copy = rec_bytes;
-        const int fit = min(static_cast<int>(Geo::kWaveBytes / rec_copy), 60 / NL);   // pieces per batch
-        const int rec_member = (bkv % p.Hkv) % p.wg;  // the piece of group g sits in the records of wave g*wg + member
+        const int fit = min(static_cast<int>(Geo::kWaveBytes / rec_bytes), 60 / NL);   // records per batch
         // A lane without a k-th group folds group 0 in its place and stores nothing for it: the loop below
         // then has no divergent parts, and the reads of a lane's groups are issued together.
         int idx[K], grp[K], qrow[K];
@@ -578,26 +619,25 @@ struct Wave {
 #pragma unroll
         for (int k = 0; k < K; ++k) { M[k] = -__builtin_inff(); den[k] = 0.f; num[k] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 
-        for (int w = w0; w <= w1; w += fit) {
-            const int nb = min(fit, w1 - w + 1);
+        for (int w = first; w <= last; w += fit) {
+            const int nb = min(fit, last - w + 1);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the LDS reads of the batch before have returned
 #pragma unroll 1
             for (int i = 0; i < nb; ++i) {
                 const int wi = w + i;
-                const int slot = (a < wi * span) ? 0 : 1;
-                const unsigned rec = static_cast<unsigned>((wi * p.wg + rec_member) * 2 + slot) * rec_bytes;
-                const char* src = scalar_ptr(reinterpret_cast<const char*>(p.partials) + rec);
-                const unsigned dst = lds_wave + static_cast<unsigned>(i) * rec_copy;
+                const int r = base + (wi * p.wg + member) * 2 + (start < wi * stride ? 0 : 1);
+                const char* src = scalar_ptr(reinterpret_cast<const char*>(p.partials) + static_cast<unsigned>(r) * rec_bytes);
+                const unsigned dst = lds_wave + static_cast<unsigned>(i) * rec_bytes;
 #pragma unroll
                 for (int j = 0; j < NL; ++j) {
                     const unsigned off = j * 1024u + lane * 16u;
-                    if (off < rec_copy) dma16_shared(dst + j * 1024u, off, src);
+                    if (off < rec_bytes) dma16_shared(dst + j * 1024u, off, src);
                 }
             }
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll 1
             for (int i = 0; i < nb; ++i) {
-                const lds_char* rec = lds_ptr + static_cast<unsigned>(i) * rec_copy;
+                const lds_char* rec = lds_ptr + static_cast<unsigned>(i) * rec_bytes;
 #pragma unroll
                 for (int k = 0; k < K; ++k) {
                     const f32x2 ml = *reinterpret_cast<const __attribute__((address_space(3))) f32x2*>(rec + (G * D + 2 * qrow[k]) * 4);
@@ -612,6 +652,17 @@ struct Wave {
                 }
             }
         }
+        if (into != kWholeStream) {
+            // a record like a wave's own: the sums as they are, and (m, l) from the lane that owns a row's first group
+            const unsigned rec = static_cast<unsigned>(2 * p.slots + into) * rec_bytes;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                if (idx[k] < 0) continue;
+                shared_store4(rec + idx[k] * 16u, num[k]);
+                if (idx[k] * 4 % D == 0) shared_store2(rec + (G * D + 2 * qrow[k]) * 4u, M[k], den[k]);
+            }
+            return;
+        }
         const int b = bkv / p.Hkv, kv = bkv % p.Hkv;
         float* o = p.out + (static_cast<size_t>(b) * p.Hq + kv * G) * D;  // the group's rows are contiguous, like the record's
 #pragma unroll
@@ -625,6 +676,7 @@ struct Wave {
 
     __amdgpu_buffer_rsrc_t records;  // the record area of the workspace
     int wave;       // index of this wave
+    int group;      // index of its group of wg waves
     int member;     // its place in its group of wg waves: it serves the kv heads congruent to member mod wg
     int span;       // group-units per group of waves
     int live;       // requests that own pages
@@ -734,7 +786,7 @@ struct Wave {
         const int first_end = first_a + first_n - u0;   // stages the first stream takes in this span, if it ends inside
         bool announced = false;
         // stages after which the piece may be announced (never reached when there is nothing to announce)
-        const int stop = (first_partial && first_end < total) ? first_end + NS - 1 : total;
+        const int stop = (first_partial && first_end < total && !two_levels(first_n)) ? first_end + NS - 1 : total;
         int base = 0;
         for (; base + kSteady < total; base += NS) {   // one copy of the steady round in the kernel's code
             if (base >= stop && !announced) {
@@ -919,6 +971,7 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
     w.lane = threadIdx.x & 63;
     w.wave = wave;
     w.member = member;
+    w.group = group;
     w.span = span;
     w.live = live;
     w.u0 = group * span;
@@ -926,7 +979,7 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(Params p, int pa
     w.lds_ptr = (lds_char*)ring + wave_in_block * W::Geo::kWaveBytes;
     w.lds_wave = static_cast<unsigned>(reinterpret_cast<uintptr_t>(w.lds_ptr));
     w.init_lane_tables();
-    w.records = __builtin_amdgcn_make_buffer_rsrc(p.partials, 0, static_cast<int>(2u * p.slots * record_floats(p.G, D) * 4u), 0x00020000);
+    w.records = __builtin_amdgcn_make_buffer_rsrc(p.partials, 0, static_cast<int>((2u * p.slots + cluster_records(p.slots)) * record_floats(p.G, D) * 4u), 0x00020000);
     w.m = 0.f;
     w.l = 0.f;
     w.cur.upos = w.u0;

@@ -45,8 +45,10 @@ struct Params {
     int32_t* req;               // [B] request id of the r-th non-empty request
     int32_t* order;             // [B] requests by decreasing prefill work
     int32_t* wave_start;        // [slots * 4] {r, kv, page, 0}
-    float* partials;            // [slots * 2] records, record_floats(G, D) floats apart: G*D accumulator values, then m and l of the G rows
-    int32_t* counters;          // [B * Hkv] arrival counters of the fused kernel (zero between calls)
+    float* partials;            // [slots * 2 + cluster_records(slots)] records, record_floats(G, D) floats apart: G*D accumulator
+                                // values, then m and l of the G rows; two per wave, then the clusters' records
+    int32_t* counters;          // [B * Hkv + cluster_records(slots)] arrival counters of the fused kernel, per stream and then
+                                // per cluster record (zero between calls)
     int32_t B, Hq, Hkv, G, D, maxp, NP, slots;
     int32_t wg;                 // waves per group in the fused kernel (divides Hkv and slots)
     float scale_log2e;          // softmax_scale * log2(e): scores are kept in the exp2 domain
@@ -58,6 +60,15 @@ inline __host__ __device__ int span_for(int units, int slots)
     int span = (units + slots - 1) / slots;
     return span < kMinSpan ? kMinSpan : span;
 }
+
+// The merge of a stream longer than kFlatMergePieces - 1 spans (kFlatMergePieces pieces or more) goes in two levels: the pieces of
+// each cluster of kMergeCluster consecutive wave groups are merged, by the last wave of the cluster to finish,
+// into one record of the same format, and the last cluster to finish merges those.  A cluster holds at most two
+// such parts per wave of a group: of a stream that began before the cluster (side 0) and of one that begins in
+// it and goes on beyond it (side 1).  cluster_records(slots) bounds ((cluster * wg + member) * 2 + side) + 1.
+constexpr int kMergeCluster = 16;
+constexpr int kFlatMergePieces = 32;
+inline __host__ __device__ int cluster_records(int slots) { return 2 * (slots / kMergeCluster) + 16; }
 
 // Floats from one partial record to the next: G*D accumulator values, then G (m, l) pairs, rounded up to a whole
 // number of 16-byte units (the merge copies records 16 bytes a lane).
