@@ -118,6 +118,40 @@ def test_reference_partition_covers_every_page_once(wg, hkv):
     assert [first[w] for w in range(nwaves)] == starts
 
 
+@pytest.mark.parametrize("wg,hkv,slots", [(8, 8, 768), (8, 8, 1024), (4, 8, 100), (2, 2, 832), (1, 5, 1024), (1, 1, 28)])
+def test_two_level_merge_records_never_collide(wg, hkv, slots):
+    """The rule of the two-level merge, stated here in plain Python and checked on the host model of the partition:
+    a sequence of one kv head that is longer than 31 spans is merged cluster by cluster (16 consecutive wave groups)
+    into record ((cluster * wg + member) * 2 + side), side 0 if the sequence began before the cluster, and the
+    library sets aside 2 * (slots // 16) + 16 such records.  Every (sequence, cluster) pair must get a record of
+    its own below that bound, and such a sequence must reach into a second cluster."""
+    cluster, flat = 16, 32
+    rng = np.random.default_rng(wg * 100 + hkv)
+    for trial in range(12):
+        B = int(rng.integers(1, 9))
+        lens = np.where(rng.random(B) < 0.6, rng.integers(6000, 70000, size=B), rng.integers(0, 300, size=B))
+        maxp = 5000
+        hdr, _, _ = partition_ref.partition(lens, hkv, slots, maxp, group_waves=wg)
+        span = hdr[1]
+        groups_of = {}
+        for w, b, kv, p0, p1 in partition_ref.segments(lens, hkv, slots, maxp, group_waves=wg):
+            groups_of.setdefault((b, kv), []).append(w // wg)
+        used = {}
+        for (b, kv), gs in groups_of.items():
+            n = partition_ref.pages(int(lens[b]), maxp)
+            if n <= (flat - 1) * span:
+                continue
+            assert gs == list(range(gs[0], gs[-1] + 1)) and len(gs) >= flat
+            w0, member = gs[0], kv % wg
+            clusters = sorted({g // cluster for g in gs})
+            assert len(clusters) >= 2
+            for c in clusters:
+                rec = (c * wg + member) * 2 + (0 if w0 < c * cluster else 1)
+                assert 0 <= rec < 2 * (slots // cluster) + 16, (rec, slots)
+                assert rec not in used, (rec, (b, kv), used[rec])
+                used[rec] = (b, kv)
+
+
 def test_generator_matches_documented_totals():
     # totals of the benchmark recipe (seed 0): a change of the generator would silently move the benchmark
     want = {2: 957_219, 3: 175_455, 4: 810_848, 5: 1_738_022}
