@@ -562,7 +562,7 @@ struct Wave {
             if (lane == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             asm volatile("" ::: "memory");  // the record loads below stay behind the counter read
             // the record of item i: of wave group i, the first of its wave's two if the piece began before that wave's
-            // span (a < i*span), the second otherwise; of cluster i, behind all of those, by the same rule (w0 < i*16)
+            // span (a < i*span), the second otherwise; of cluster i, behind all of those, by the same rule (w0 < i*8)
             merge(bkv, first, last, from_clusters ? 2 * p.slots : 0, from_clusters ? w0 : a, from_clusters ? kMergeCluster : span, into);
             if (into == kWholeStream) return;
             // second level: the cluster's record is complete in memory before the cluster is counted

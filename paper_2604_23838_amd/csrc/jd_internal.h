@@ -66,8 +66,8 @@ inline __host__ __device__ int span_for(int units, int slots)
 // into one record of the same format, and the last cluster to finish merges those.  A cluster holds at most two
 // such parts per wave of a group: of a stream that began before the cluster (side 0) and of one that begins in
 // it and goes on beyond it (side 1).  cluster_records(slots) bounds ((cluster * wg + member) * 2 + side) + 1.
-constexpr int kMergeCluster = 16;
-constexpr int kFlatMergePieces = 32;
+constexpr int kMergeCluster = 8;
+constexpr int kFlatMergePieces = 16;
 inline __host__ __device__ int cluster_records(int slots) { return 2 * (slots / kMergeCluster) + 16; }
 
 // Floats from one partial record to the next: G*D accumulator values, then G (m, l) pairs, rounded up to a whole

@@ -165,8 +165,8 @@ def test_cu_budget_changes_split_not_result(torch_cuda, jo):
 
 @pytest.mark.parametrize("hq,hkv,d", [(32, 8, 128), (14, 2, 64), (5, 5, 64), (16, 1, 128)])   # wave groups of 8, 2, 1, 1
 def test_two_level_merge_at_many_splits(torch_cuda, jo, hq, hkv, d):
-    # sequences cut into far more than 32 pieces are merged cluster by cluster (16 wave groups each) and then over the
-    # clusters; the CU budget moves the span, hence where the pieces, the cluster borders and the 32-piece limit fall:
+    # sequences cut into 16 pieces or more are merged cluster by cluster (8 wave groups each) and then over the
+    # clusters; the CU budget moves the span, hence where the pieces, the cluster borders and the 16-piece limit fall:
     # long sequences that begin and end at every kind of place, short ones in between, twice on one handle
     lens = np.array([40000, 3, 25000, 100, 0, 17000, 17, 9000], dtype=np.int32)
     w = W.build(W.Shape("t", 0, hq, hkv, d, 1), lens, seed=31, cfg=93)

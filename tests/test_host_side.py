@@ -121,11 +121,11 @@ def test_reference_partition_covers_every_page_once(wg, hkv):
 @pytest.mark.parametrize("wg,hkv,slots", [(8, 8, 768), (8, 8, 1024), (4, 8, 100), (2, 2, 832), (1, 5, 1024), (1, 1, 28)])
 def test_two_level_merge_records_never_collide(wg, hkv, slots):
     """The rule of the two-level merge, stated here in plain Python and checked on the host model of the partition:
-    a sequence of one kv head that is longer than 31 spans is merged cluster by cluster (16 consecutive wave groups)
+    a sequence of one kv head that is longer than 15 spans is merged cluster by cluster (8 consecutive wave groups)
     into record ((cluster * wg + member) * 2 + side), side 0 if the sequence began before the cluster, and the
-    library sets aside 2 * (slots // 16) + 16 such records.  Every (sequence, cluster) pair must get a record of
+    library sets aside 2 * (slots // 8) + 16 such records.  Every (sequence, cluster) pair must get a record of
     its own below that bound, and such a sequence must reach into a second cluster."""
-    cluster, flat = 16, 32
+    cluster, flat = 8, 16
     rng = np.random.default_rng(wg * 100 + hkv)
     for trial in range(12):
         B = int(rng.integers(1, 9))
